@@ -1,0 +1,281 @@
+"""Python binding of libeagle (argument marshalling only -- every step of the path runs in the HIP library).
+
+PyTorch is used for device memory (the workspace, staging of weights) and the stream, nothing else.
+The names mirror the C ABI in include/eagle.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libeagle.so")
+
+EAGLE_F32, EAGLE_BF16 = 0, 1
+HEAD_LAYER = -1
+(W_EMBED, W_LM_HEAD, W_FINAL_NORM, W_FC, W_FC_BIAS, W_ATTN_NORM, W_Q, W_K, W_V, W_O, W_MLP_NORM, W_ROUTER,
+ W_GATE, W_UP, W_DOWN) = range(15)
+(BUF_LOGITS, BUF_FEATURES, BUF_DRAFT_LOGITS, BUF_DRAFT_FEATURES, BUF_TREE_TOKENS, BUF_TOKENS, BUF_VANILLA_LOGITS,
+ BUF_STATE) = range(8)
+
+_LAYER_IDS = {"attn_norm": W_ATTN_NORM, "wq": W_Q, "wk": W_K, "wv": W_V, "wo": W_O, "mlp_norm": W_MLP_NORM,
+              "router": W_ROUTER, "gate": W_GATE, "up": W_UP, "down": W_DOWN}
+_GLOBAL_IDS = {"embed": W_EMBED, "lm_head": W_LM_HEAD, "final_norm": W_FINAL_NORM, "head.fc_w": W_FC,
+               "head.fc_b": W_FC_BIAS}
+
+EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weight", "eagle_reset", "eagle_prefill",
+           "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_step", "eagle_vanilla_step", "eagle_generate",
+           "eagle_set_hint", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile",
+           "eagle_last_error", "eagle_version"]
+
+
+class EagleConfig(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32),
+                ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("d_ffn", ctypes.c_int32), ("vocab", ctypes.c_int32), ("n_experts", ctypes.c_int32),
+                ("experts_per_tok", ctypes.c_int32), ("draft_moe", ctypes.c_int32), ("rms_eps", ctypes.c_float),
+                ("rope_theta", ctypes.c_float), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
+                ("page_tokens", ctypes.c_int32), ("n_nodes", ctypes.c_int32),
+                ("parent", ctypes.POINTER(ctypes.c_int32)), ("rank", ctypes.POINTER(ctypes.c_int32)),
+                ("temperature", ctypes.c_float), ("seed", ctypes.c_uint64)]
+
+
+class EagleProfile(ctypes.Structure):
+    _fields_ = [("draft_ms", ctypes.c_double), ("verify_ms", ctypes.c_double), ("accept_ms", ctypes.c_double),
+                ("steps", ctypes.c_int64), ("gemm_ms", ctypes.c_double), ("gemm_launches", ctypes.c_int64),
+                ("gemm_weight_bytes", ctypes.c_double), ("verify_weight_bytes", ctypes.c_double),
+                ("verify_kv_bytes", ctypes.c_double)]
+
+
+class EagleError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libeagle error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library(need_gpu_runtime: bool = True):
+    """dlopen libeagle.so.  torch is imported first so that the HIP runtime it ships is the one in the process."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(there is no fallback path)")
+    if need_gpu_runtime:
+        import torch  # noqa: F401  (loads libamdhip64)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    pi32 = ctypes.POINTER(ctypes.c_int32)
+    lib.eagle_workspace_bytes.argtypes = [ctypes.POINTER(EagleConfig)]
+    lib.eagle_workspace_bytes.restype = sz
+    lib.eagle_init.argtypes = [ctypes.POINTER(EagleConfig), vp, sz, vp, ctypes.POINTER(vp)]
+    lib.eagle_free.argtypes = [vp]
+    lib.eagle_free.restype = None
+    lib.eagle_load_weight.argtypes = [vp, i32, i32, vp]
+    lib.eagle_reset.argtypes = [vp]
+    lib.eagle_prefill.argtypes = [vp, i32, pi32, i32, pi32]
+    lib.eagle_draft_tree.argtypes = [vp, pi32]
+    lib.eagle_verify.argtypes = [vp]
+    lib.eagle_accept.argtypes = [vp, pi32, pi32, pi32]
+    lib.eagle_step.argtypes = [vp, pi32, pi32, pi32]
+    lib.eagle_vanilla_step.argtypes = [vp, pi32]
+    lib.eagle_generate.argtypes = [vp, i32, pi32, i32, i32, pi32, pi32, ctypes.POINTER(ctypes.c_float)]
+    lib.eagle_set_hint.argtypes = [vp, i32, pi32, i32, ctypes.c_float, ctypes.c_float, ctypes.c_uint64]
+    lib.eagle_get_buffer.argtypes = [vp, i32, i32, vp, sz]
+    lib.eagle_get_kv_row.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+    lib.eagle_set_profiling.argtypes = [vp, i32]
+    lib.eagle_get_profile.argtypes = [vp, ctypes.POINTER(EagleProfile), i32]
+    lib.eagle_last_error.restype = ctypes.c_char_p
+    lib.eagle_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _p32(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0):
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    rank = np.ascontiguousarray(rank, dtype=np.int32)
+    cfg = EagleConfig(dtype=EAGLE_F32 if shape.dtype == "fp32" else EAGLE_BF16, n_layers=shape.n_layers,
+                      d_model=shape.d_model, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads,
+                      head_dim=shape.head_dim, d_ffn=shape.d_ffn, vocab=shape.vocab, n_experts=shape.n_experts,
+                      experts_per_tok=shape.experts_per_tok, draft_moe=int(shape.draft_moe), rms_eps=shape.rms_eps,
+                      rope_theta=shape.rope_theta, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
+                      n_nodes=len(parent), parent=_p32(parent), rank=_p32(rank), temperature=temperature, seed=seed)
+    cfg._keep = (parent, rank)
+    return cfg
+
+
+class Eagle:
+    """One libeagle context on cuda:0 (ROCm).  Methods are the C calls, with numpy in/out."""
+
+    def __init__(self, shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libeagle needs a GPU (no CPU fallback exists)")
+        self.shape, self.device = shape, torch.device(device)
+        self.cfg = make_config(shape, parent, rank, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
+                               temperature=temperature, seed=seed)
+        self.M = len(parent)
+        depth = [0] * self.M
+        for v in range(1, self.M):
+            depth[v] = depth[int(parent[v])] + 1
+        self.D = max(depth)
+        self.max_batch = max_batch
+        need = self.lib.eagle_workspace_bytes(ctypes.byref(self.cfg))
+        if need == 0:
+            raise EagleError(-1, self.lib.eagle_last_error().decode())
+        self.workspace_bytes = need
+        self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        self.stream = torch.cuda.current_stream(self.device)
+        h = ctypes.c_void_p()
+        self._chk(self.lib.eagle_init(ctypes.byref(self.cfg), base, need, self.stream.cuda_stream, ctypes.byref(h)))
+        self.h = h
+        self.n_active = 0
+
+    def _chk(self, rc: int) -> None:
+        if rc != 0:
+            raise EagleError(rc, self.lib.eagle_last_error().decode())
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            self.lib.eagle_free(self.h)
+            self.h = None
+            self.workspace = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- weights
+    def load_weight(self, which: int, layer: int, host: np.ndarray) -> None:
+        """Stage one host tensor on the device (torch), hand it to the library, release the staging copy."""
+        torch = self.torch
+        t = torch.from_numpy(np.ascontiguousarray(host))
+        if t.dtype == torch.uint16:
+            t = t.view(torch.int16)
+        dev = t.to(self.device, non_blocking=False)
+        self._chk(self.lib.eagle_load_weight(self.h, which, layer, dev.data_ptr()))
+        torch.cuda.current_stream(self.device).synchronize()
+        del dev
+
+    def load_named(self, name: str, host: np.ndarray) -> None:
+        if name in _GLOBAL_IDS:
+            self.load_weight(_GLOBAL_IDS[name], 0, host)
+            return
+        parts = name.split(".")
+        if parts[0] == "layers":
+            self.load_weight(_LAYER_IDS[parts[2]], int(parts[1]), host)
+        elif parts[0] == "head" and parts[1] == "layer":
+            self.load_weight(_LAYER_IDS[parts[2]], HEAD_LAYER, host)
+        else:
+            raise KeyError(name)
+
+    def load_weights(self, named) -> None:
+        """named: iterable of (name, host array) in the model's dtype (fp32, or raw bf16 bits as uint16;
+        norm gains and the FC bias always fp32)."""
+        items = named.items() if isinstance(named, dict) else named
+        for name, arr in items:
+            self.load_named(name, arr)
+
+    # -- sequences
+    def reset(self) -> None:
+        self._chk(self.lib.eagle_reset(self.h))
+        self.n_active = 0
+
+    def prefill(self, seq: int, prompt: Sequence[int]) -> int:
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        first = ctypes.c_int32()
+        self._chk(self.lib.eagle_prefill(self.h, seq, _p32(p), len(p), ctypes.byref(first)))
+        self.n_active = max(self.n_active, seq + 1)
+        return int(first.value)
+
+    def set_hint(self, seq: int, future: Sequence[int], alpha: float, bias: float, seed: int) -> None:
+        f = np.ascontiguousarray(future, dtype=np.int32)
+        self._chk(self.lib.eagle_set_hint(self.h, seq, _p32(f), len(f), alpha, bias, seed))
+
+    def draft_tree(self) -> np.ndarray:
+        out = np.zeros((self.n_active, self.M), np.int32)
+        self._chk(self.lib.eagle_draft_tree(self.h, _p32(out)))
+        return out
+
+    def verify(self) -> None:
+        self._chk(self.lib.eagle_verify(self.h))
+
+    def _results(self, fn):
+        toks = np.zeros((self.n_active, self.D + 1), np.int32)
+        lens = np.zeros(self.n_active, np.int32)
+        path = np.zeros((self.n_active, self.D + 1), np.int32)
+        self._chk(fn(self.h, _p32(toks), _p32(lens), _p32(path)))
+        return toks, lens, path
+
+    def accept(self):
+        return self._results(self.lib.eagle_accept)
+
+    def step(self):
+        return self._results(self.lib.eagle_step)
+
+    def vanilla_step(self) -> np.ndarray:
+        out = np.zeros(self.n_active, np.int32)
+        self._chk(self.lib.eagle_vanilla_step(self.h, _p32(out)))
+        return out
+
+    def generate(self, prompt: Sequence[int], max_new: int):
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.zeros(max_new, np.int32)
+        n = ctypes.c_int32()
+        tau = ctypes.c_float()
+        self._chk(self.lib.eagle_generate(self.h, 0, _p32(p), len(p), max_new, _p32(out), ctypes.byref(n), ctypes.byref(tau)))
+        self.n_active = 1
+        return out[:n.value].copy(), float(tau.value)
+
+    # -- buffers
+    def get_buffer(self, which: int, seq: int = 0) -> np.ndarray:
+        V, d, M = self.shape.vocab, self.shape.d_model, self.M
+        if which in (BUF_LOGITS, BUF_DRAFT_LOGITS):
+            out = np.empty((M, V), np.float32)
+        elif which in (BUF_FEATURES, BUF_DRAFT_FEATURES):
+            out = np.empty((M, d), np.float32)
+        elif which == BUF_TREE_TOKENS:
+            out = np.empty(M, np.int32)
+        elif which == BUF_VANILLA_LOGITS:
+            out = np.empty(V, np.float32)
+        elif which == BUF_STATE:
+            out = np.empty(4, np.int32)
+        elif which == BUF_TOKENS:
+            n = int(self.get_buffer(BUF_STATE, seq)[0])
+            out = np.empty(n, np.int32)
+        else:
+            raise ValueError(which)
+        self._chk(self.lib.eagle_get_buffer(self.h, which, seq, out.ctypes.data, out.nbytes))
+        return out
+
+    def get_kv_row(self, seq: int, layer: int, pos: int):
+        n = self.shape.n_kv_heads * self.shape.head_dim
+        k = np.empty(n, np.float32)
+        v = np.empty(n, np.float32)
+        fp = ctypes.POINTER(ctypes.c_float)
+        self._chk(self.lib.eagle_get_kv_row(self.h, seq, layer, pos, k.ctypes.data_as(fp), v.ctypes.data_as(fp)))
+        return k, v
+
+    def set_profiling(self, mode: int) -> None:
+        self._chk(self.lib.eagle_set_profiling(self.h, mode))
+
+    def get_profile(self, reset: bool = True) -> Dict[str, float]:
+        p = EagleProfile()
+        self._chk(self.lib.eagle_get_profile(self.h, ctypes.byref(p), int(reset)))
+        return {f: getattr(p, f) for f, _ in p._fields_}

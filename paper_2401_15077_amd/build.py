@@ -1,0 +1,38 @@
+"""Build libeagle.so (hipcc, gfx950) in-tree."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libeagle.so")
+SOURCES = ["eagle.hip"]
+HEADERS = ["kernels.h", "common.h", os.path.join("..", "..", "include", "eagle.h")]
+
+
+def needs_build() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    """Compile every HIP source for gfx950 into libeagle.so.  Raises on failure."""
+    if not force and not needs_build():
+        return LIB
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-result", "-Wno-unused-command-line-argument",
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if verbose or res.returncode:
+        print(err)
+    if res.returncode:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

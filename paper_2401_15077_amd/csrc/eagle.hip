@@ -1,0 +1,887 @@
+// libeagle: host side -- context, workspace layout, weight loading, and the orchestration of one EAGLE
+// speculative step (drafting: Sec. 3.1 / App. A.1; verification: Sec. 3.3; acceptance: Sec. 2 / App. A.2).
+#include "../../include/eagle.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+static thread_local char g_err[512] = "";
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+#define HIPCHK(x)                                                                                         \
+  do {                                                                                                    \
+    hipError_t e_ = (x);                                                                                  \
+    if (e_ != hipSuccess) return fail(EAGLE_EHIP, "%s failed: %s (%s:%d)", #x, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+#define LAUNCH_CHECK() HIPCHK(hipGetLastError())
+
+// ---------------------------------------------------------------------------- descriptors
+struct PackedW {            // a weight matrix in tiled layout
+  bf16_t* w = nullptr;
+  size_t plane_stride = 0;  // elements between planes
+  int N = 0, Npad = 0, NRB = 0, K = 0, KS = 0;
+};
+struct LayerW {
+  PackedW qkv, o, gu, dn;
+  std::vector<PackedW> e_gu, e_dn;   // MoE experts
+  float* router = nullptr;           // fp32 [E][d]
+  float *attn_norm = nullptr, *mlp_norm = nullptr;
+  bool moe = false;
+};
+struct GemmPlan { int S, ks_per_split, chunk; };
+
+struct Arena {
+  char* base; size_t off = 0;
+  explicit Arena(char* b) : base(b) {}
+  template <typename T> T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = (T*)(base + off);
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct eagle_ctx {
+  eagle_config cfg;
+  hipStream_t stream;
+  char* ws; size_t ws_bytes;
+  bool f32;
+  int NWP, NXP, elt;                 // weight planes, activation planes, bytes per model-dtype element
+  TreeDev tree_h; TreeDev* tree_d;
+  int M, D, Mmax, max_level_rows;
+  // weights
+  void* embed; PackedW lm_head, fc; float *final_norm, *fc_bias;
+  std::vector<LayerW> layers;        // [n_layers] target + [1] head
+  bool loaded[EAGLE_W_COUNT][2];
+  std::vector<std::vector<char>> loaded_layer;  // [which][layer+1]
+  // caches
+  void *kc, *vc, *dkc, *dvc; size_t layer_stride; int* page_table; int pps, page_shift;
+  float *rope_cos, *rope_sin;
+  // state
+  SeqState st; HintDev hint;
+  int *hint_future, *hint_n; float *hint_alpha, *hint_bias; unsigned long long* hint_seed;
+  float *pend_f, *node_f, *F, *chunk_f, *featbuf;
+  float *draft_logits, *L, *vanilla_logits, *pbuf, *qbuf, *gumbel;
+  int *tree_tok, *on_path, *path, *tok_out, *len_out;
+  // activations
+  float *h, *Q, *PT, *part_o, *part_ml;
+  bf16_t *xf_d, *xf_2d, *xf_att, *xf_ffn;
+  size_t pt_floats;
+  // host mirror
+  std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
+  int n_active = 0;
+  int phase = 0;                      // 0 idle, 1 drafted, 2 verified
+  // profiling
+  int prof_mode = 0;
+  hipEvent_t ev[4];
+  std::vector<hipEvent_t> gemm_ev; size_t gemm_ev_used = 0; std::vector<double> gemm_ev_bytes;
+  eagle_profile prof;
+};
+
+static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
+  GemmPlan p;
+  int wg_n = (NRB + 3) / 4;
+  int S = std::max(1, std::min(16, 512 / std::max(1, wg_n)));
+  S = std::min(S, std::max(1, KS / 8));
+  p.ks_per_split = (KS + S - 1) / S;
+  p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
+  p.chunk = std::max(1, 64 / (NXP * MT));
+  return p;
+}
+
+static int build_tree(const eagle_config* cfg, TreeDev* t) {
+  int M = cfg->n_nodes;
+  if (M < 1 || M > EAGLE_MAX_NODES) return fail(EAGLE_EINVAL, "n_nodes must be 1..%d", EAGLE_MAX_NODES);
+  if (!cfg->parent || !cfg->rank) return fail(EAGLE_EINVAL, "parent/rank arrays missing");
+  memset(t, 0, sizeof(*t));
+  t->M = M;
+  if (cfg->parent[0] != -1) return fail(EAGLE_EINVAL, "node 0 must be the root (parent -1)");
+  t->parent[0] = -1; t->anc[0] = 1ull;
+  for (int v = 1; v < M; ++v) {
+    int p = cfg->parent[v];
+    if (p < 0 || p >= v) return fail(EAGLE_EINVAL, "parent[%d]=%d must precede its child", v, p);
+    t->parent[v] = p; t->depth[v] = t->depth[p] + 1;
+    if (t->depth[v] < t->depth[v - 1]) return fail(EAGLE_EINVAL, "nodes must be in BFS order");
+    if (t->depth[v] > EAGLE_MAX_DEPTH) return fail(EAGLE_EINVAL, "tree deeper than %d", EAGLE_MAX_DEPTH);
+    t->anc[v] = t->anc[p] | (1ull << v);
+    int r = cfg->rank[v];
+    if (r < 0 || r >= EAGLE_MAX_CHILD) return fail(EAGLE_EINVAL, "rank[%d]=%d out of range", v, r);
+    t->child[p][r] = v; t->nchild[p]++;
+    if (t->depth[v] > t->D) t->D = t->depth[v];
+  }
+  for (int v = 0; v < M; ++v) {       // sibling ranks must be exactly 0..k-1
+    unsigned seen = 0;
+    for (int c = 1; c < M; ++c) if (t->parent[c] == v) {
+      if (cfg->rank[c] >= t->nchild[v] || (seen >> cfg->rank[c]) & 1u) return fail(EAGLE_EINVAL, "sibling ranks of node %d are not 0..k-1", v);
+      seen |= 1u << cfg->rank[c];
+    }
+    if (t->nchild[v] > 0 && t->depth[v] >= 1) t->level_rows[t->depth[v]][t->n_level_rows[t->depth[v]]++] = v;
+  }
+  return EAGLE_OK;
+}
+
+static int check_cfg(const eagle_config* c) {
+  if (!c) return fail(EAGLE_EINVAL, "null config");
+  if (c->dtype != EAGLE_F32 && c->dtype != EAGLE_BF16) return fail(EAGLE_EINVAL, "dtype must be EAGLE_F32 or EAGLE_BF16");
+  if (c->n_layers < 1 || c->d_model < 16 || c->d_model % 16) return fail(EAGLE_EINVAL, "d_model must be a positive multiple of 16");
+  if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 32) return fail(EAGLE_EINVAL, "head_dim must be 32, 64 or 128");
+  if (c->n_heads < 1 || c->n_kv_heads < 1 || c->n_heads % c->n_kv_heads) return fail(EAGLE_EINVAL, "n_heads must be a multiple of n_kv_heads");
+  if ((c->n_heads * c->head_dim) % 32 || (c->n_kv_heads * c->head_dim) % 32) return fail(EAGLE_EINVAL, "attention widths must be multiples of 32");
+  if (c->d_ffn < 16 || c->d_ffn % 16) return fail(EAGLE_EINVAL, "d_ffn must be a multiple of 16");
+  if (c->vocab < 2) return fail(EAGLE_EINVAL, "vocab too small");
+  if (c->n_experts < 0 || c->n_experts > 64 || (c->n_experts > 0 && (c->experts_per_tok < 1 || c->experts_per_tok > c->n_experts || c->experts_per_tok > 4)))
+    return fail(EAGLE_EINVAL, "bad expert counts");
+  if (c->max_batch < 1 || c->max_batch > 64) return fail(EAGLE_EINVAL, "max_batch must be 1..64");
+  if (c->page_tokens < 16 || (c->page_tokens & (c->page_tokens - 1))) return fail(EAGLE_EINVAL, "page_tokens must be a power of two >= 16");
+  if (c->max_seq < c->n_nodes + 2) return fail(EAGLE_EINVAL, "max_seq too small for the tree");
+  if (!(c->temperature >= 0.f)) return fail(EAGLE_EINVAL, "temperature must be >= 0");
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(EAGLE_EINVAL, "bad rms_eps / rope_theta");
+  return EAGLE_OK;
+}
+
+static void take_packed(Arena& a, PackedW& w, int N, int K, int NWP) {
+  w.N = N; w.K = K; w.Npad = (N + 31) / 32 * 32; w.NRB = w.Npad / 32; w.KS = K / 16;
+  w.plane_stride = (size_t)w.Npad * K;
+  w.w = a.take<bf16_t>(w.plane_stride * NWP);
+}
+
+// Lays the context's buffers out in the workspace (or just measures when c->ws == nullptr).
+static size_t layout(eagle_ctx* c) {
+  const eagle_config& g = c->cfg;
+  Arena a(c->ws);
+  const int d = g.d_model, V = g.vocab, H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn, B = g.max_batch;
+  const int M = c->M, D1 = c->D + 1;
+  const int Fpad = (F + 31) / 32 * 32;     // the up rows start on a 32-row tile boundary
+  c->tree_d = a.take<TreeDev>(1);
+  c->rope_cos = a.take<float>((size_t)g.max_seq * dh / 2);
+  c->rope_sin = a.take<float>((size_t)g.max_seq * dh / 2);
+  // weights
+  c->embed = a.take<char>((size_t)V * d * c->elt);
+  take_packed(a, c->lm_head, V, d, c->NWP);
+  take_packed(a, c->fc, d, 2 * d, c->NWP);
+  c->final_norm = a.take<float>(d);
+  c->fc_bias = a.take<float>(d);
+  c->layers.assign(g.n_layers + 1, LayerW());
+  for (int l = 0; l <= g.n_layers; ++l) {
+    LayerW& w = c->layers[l];
+    take_packed(a, w.qkv, (H + 2 * KVH) * dh, d, c->NWP);
+    take_packed(a, w.o, d, H * dh, c->NWP);
+    w.moe = g.n_experts > 0 && (l < g.n_layers || g.draft_moe);
+    if (w.moe) {
+      w.e_gu.resize(g.n_experts); w.e_dn.resize(g.n_experts);
+      for (int e = 0; e < g.n_experts; ++e) { take_packed(a, w.e_gu[e], Fpad + F, d, c->NWP); take_packed(a, w.e_dn[e], d, F, c->NWP); }
+      w.router = a.take<float>((size_t)g.n_experts * d);
+    } else {
+      take_packed(a, w.gu, Fpad + F, d, c->NWP);
+      take_packed(a, w.dn, d, F, c->NWP);
+    }
+    w.attn_norm = a.take<float>(d);
+    w.mlp_norm = a.take<float>(d);
+  }
+  // KV pages
+  c->pps = (g.max_seq + g.page_tokens - 1) / g.page_tokens;
+  c->page_shift = 0;
+  while ((1 << c->page_shift) < g.page_tokens) c->page_shift++;
+  c->layer_stride = (size_t)B * c->pps * KVH * g.page_tokens * dh;
+  c->kc = a.take<char>(c->layer_stride * g.n_layers * c->elt);
+  c->vc = a.take<char>(c->layer_stride * g.n_layers * c->elt);
+  c->dkc = a.take<char>(c->layer_stride * c->elt);
+  c->dvc = a.take<char>(c->layer_stride * c->elt);
+  c->page_table = a.take<int>((size_t)B * c->pps);
+  // state
+  c->st.ctx_len = a.take<int>(B); c->st.n_pend = a.take<int>(B); c->st.n_tok = a.take<int>(B);
+  c->st.step_no = a.take<int>(B); c->st.commit_base = a.take<int>(B);
+  c->st.tok_stride = g.max_seq + 8;
+  c->st.tokens = a.take<int>((size_t)B * c->st.tok_stride);
+  c->hint_future = a.take<int>((size_t)B * c->st.tok_stride);
+  c->hint_n = a.take<int>(B); c->hint_alpha = a.take<float>(B); c->hint_bias = a.take<float>(B);
+  c->hint_seed = a.take<unsigned long long>(B);
+  c->pend_f = a.take<float>((size_t)B * D1 * d);
+  c->node_f = a.take<float>((size_t)B * M * d);
+  c->F = a.take<float>((size_t)B * M * d);
+  c->chunk_f = a.take<float>((size_t)EAGLE_PREFILL_CHUNK * d);
+  c->featbuf = a.take<float>((size_t)c->Mmax * d);
+  c->draft_logits = a.take<float>((size_t)B * M * V);
+  c->L = a.take<float>((size_t)B * M * V);
+  c->vanilla_logits = a.take<float>((size_t)B * V);
+  c->pbuf = a.take<float>((size_t)B * V);
+  c->qbuf = a.take<float>((size_t)B * V);
+  c->gumbel = a.take<float>(g.temperature > 0.f ? (size_t)B * std::max(1, c->max_level_rows) * V : 1);
+  c->tree_tok = a.take<int>((size_t)B * M); c->on_path = a.take<int>((size_t)B * M);
+  c->path = a.take<int>((size_t)B * D1); c->tok_out = a.take<int>((size_t)B * D1); c->len_out = a.take<int>(B);
+  // activations
+  const int Mm = c->Mmax, MTm = Mm / 32;
+  c->h = a.take<float>((size_t)Mm * d);
+  c->Q = a.take<float>((size_t)Mm * H * dh);
+  c->xf_d = a.take<bf16_t>((size_t)c->NXP * Mm * d);
+  c->xf_2d = a.take<bf16_t>((size_t)c->NXP * Mm * 2 * d);
+  c->xf_att = a.take<bf16_t>((size_t)c->NXP * Mm * H * dh);
+  c->xf_ffn = a.take<bf16_t>((size_t)c->NXP * Mm * F);
+  // split-K partials: the largest S*Npad over all GEMM shapes, times Mmax
+  size_t worst = 0;
+  auto consider = [&](const PackedW& w) {
+    for (int mt = 1; mt <= MTm; ++mt) {
+      GemmPlan p = plan_gemm(w.NRB, w.KS, c->NXP, mt);
+      worst = std::max(worst, (size_t)p.S * w.Npad * (size_t)(mt * 32));
+    }
+  };
+  consider(c->lm_head); consider(c->fc);
+  for (auto& w : c->layers) {
+    consider(w.qkv); consider(w.o);
+    if (w.moe) { consider(w.e_gu[0]); consider(w.e_dn[0]); } else { consider(w.gu); consider(w.dn); }
+  }
+  c->pt_floats = worst;
+  c->PT = a.take<float>(worst);
+  c->part_o = a.take<float>((size_t)Mm * H * 16 * dh);
+  c->part_ml = a.take<float>((size_t)Mm * H * 16 * 2);
+  return (a.off + 255) & ~(size_t)255;
+}
+
+static int prepare(const eagle_config* cfg, eagle_ctx* c) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  c->cfg = *cfg;
+  rc = build_tree(cfg, &c->tree_h);
+  if (rc) return rc;
+  c->f32 = cfg->dtype == EAGLE_F32;
+  c->NWP = c->f32 ? 3 : 1; c->NXP = c->f32 ? 3 : 2; c->elt = c->f32 ? 4 : 2;
+  c->M = c->tree_h.M; c->D = c->tree_h.D;
+  c->max_level_rows = 1;
+  for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
+  int rows = std::max(EAGLE_PREFILL_CHUNK, cfg->max_batch * c->M);
+  c->Mmax = (rows + 31) / 32 * 32;
+  if (c->Mmax > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
+  return EAGLE_OK;
+}
+
+extern "C" size_t eagle_workspace_bytes(const eagle_config* cfg) {
+  eagle_ctx tmp{};
+  if (prepare(cfg, &tmp)) return 0;
+  tmp.ws = nullptr;
+  return layout(&tmp);
+}
+
+extern "C" const char* eagle_last_error(void) { return g_err; }
+extern "C" const char* eagle_version(void) { return "libeagle 0.1 (gfx950)"; }
+
+extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t workspace_bytes, void* hip_stream, eagle_ctx** out) {
+  if (!out) return fail(EAGLE_EINVAL, "out is null");
+  *out = nullptr;
+  eagle_ctx* c = new eagle_ctx();
+  int rc = prepare(cfg, c);
+  if (rc) { delete c; return rc; }
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete c; return fail(EAGLE_EINVAL, "workspace must be a 256-byte aligned device pointer"); }
+  c->ws = nullptr;
+  size_t need = layout(c);
+  if (workspace_bytes < need) { delete c; return fail(EAGLE_ENOMEM, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need); }
+  c->ws = (char*)workspace_dev; c->ws_bytes = workspace_bytes;
+  layout(c);
+  c->stream = (hipStream_t)hip_stream;
+  const eagle_config& g = c->cfg;
+  // the tree arrays are copied: the caller's pointers need not outlive this call
+  c->cfg.parent = nullptr; c->cfg.rank = nullptr;
+  memset(c->loaded, 0, sizeof(c->loaded));
+  c->loaded_layer.assign(EAGLE_W_COUNT, std::vector<char>(g.n_layers + 1, 0));
+  c->h_ctx.assign(g.max_batch, 0); c->h_ntok.assign(g.max_batch, 0); c->active.assign(g.max_batch, 0); c->head_stale.assign(g.max_batch, 0);
+  // zero everything that is not a weight (finite garbage-free caches and padding rows)
+  char* z0 = (char*)c->kc;
+  size_t zbytes = (size_t)(c->ws + need - z0);
+  k_fill_u32<<<2048, 256, 0, c->stream>>>((uint32_t*)z0, 0u, zbytes / 4);
+  if (hipGetLastError() != hipSuccess) { delete c; return fail(EAGLE_EHIP, "fill launch failed"); }
+  if (hipMemcpyAsync(c->tree_d, &c->tree_h, sizeof(TreeDev), hipMemcpyHostToDevice, c->stream) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "tree upload failed"); }
+  // RoPE tables: angle = pos * theta^(-2i/dh) formed in fp64, rounded once to fp32
+  {
+    const int half = g.head_dim / 2;
+    std::vector<float> cs((size_t)g.max_seq * half), sn((size_t)g.max_seq * half);
+    for (int p = 0; p < g.max_seq; ++p)
+      for (int i = 0; i < half; ++i) {
+        double ang = (double)p * std::pow((double)g.rope_theta, -2.0 * i / g.head_dim);
+        cs[(size_t)p * half + i] = (float)std::cos(ang);
+        sn[(size_t)p * half + i] = (float)std::sin(ang);
+      }
+    if (hipMemcpyAsync(c->rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipMemcpyAsync(c->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "rope table upload failed"); }
+  }
+  {  // static paging: logical page lp of slot s lives in physical page lp*max_batch + s (interleaved on purpose)
+    std::vector<int> pt((size_t)g.max_batch * c->pps);
+    for (int s = 0; s < g.max_batch; ++s)
+      for (int lp = 0; lp < c->pps; ++lp) pt[(size_t)s * c->pps + lp] = lp * g.max_batch + s;
+    if (hipMemcpyAsync(c->page_table, pt.data(), pt.size() * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "page table upload failed"); }
+  }
+  c->hint.future = c->hint_future; c->hint.stride = c->st.tok_stride; c->hint.n = c->hint_n;
+  c->hint.alpha = c->hint_alpha; c->hint.bias = c->hint_bias; c->hint.seed = c->hint_seed;
+  for (int i = 0; i < 4; ++i)
+    if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "event creation failed"); }
+  memset(&c->prof, 0, sizeof(c->prof));
+  *out = c;
+  return EAGLE_OK;
+}
+
+extern "C" void eagle_free(eagle_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+  for (auto e : c->gemm_ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+// ---------------------------------------------------------------------------- weights
+static int pack_into(eagle_ctx* c, const void* src, PackedW& w, int N, int K, int row_offset) {
+  if (K != w.K || row_offset % 32 || row_offset + N > w.Npad) return fail(EAGLE_EINVAL, "internal: pack shape mismatch");
+  size_t total = (size_t)((N + 31) / 32) * w.KS * 64;
+  int blocks = (int)((total + 255) / 256);
+  if (c->f32) k_pack_weight<float><<<blocks, 256, 0, c->stream>>>((const float*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride);
+  else k_pack_weight<bf16_t><<<blocks, 256, 0, c->stream>>>((const bf16_t*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride);
+  LAUNCH_CHECK();
+  return EAGLE_OK;
+}
+
+__global__ void k_to_f32(const bf16_t* src, float* dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = bf16_to_f32(src[i]);
+}
+
+extern "C" int eagle_load_weight(eagle_ctx* c, int32_t which, int32_t layer, const void* src) {
+  if (!c || !src) return fail(EAGLE_EINVAL, "null argument");
+  if (which < 0 || which >= EAGLE_W_COUNT) return fail(EAGLE_EINVAL, "unknown tensor id %d", which);
+  const eagle_config& g = c->cfg;
+  const int d = g.d_model, H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn, Fpad = (F + 31) / 32 * 32;
+  int rc = EAGLE_OK;
+  if (which < EAGLE_W_ATTN_NORM) {
+    switch (which) {
+      case EAGLE_W_EMBED: HIPCHK(hipMemcpyAsync(c->embed, src, (size_t)g.vocab * d * c->elt, hipMemcpyDeviceToDevice, c->stream)); break;
+      case EAGLE_W_LM_HEAD: rc = pack_into(c, src, c->lm_head, g.vocab, d, 0); break;
+      case EAGLE_W_FINAL_NORM: HIPCHK(hipMemcpyAsync(c->final_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
+      case EAGLE_W_FC: rc = pack_into(c, src, c->fc, d, 2 * d, 0); break;
+      case EAGLE_W_FC_BIAS: HIPCHK(hipMemcpyAsync(c->fc_bias, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
+    }
+    if (rc) return rc;
+    c->loaded_layer[which][0] = 1;
+    return EAGLE_OK;
+  }
+  int li = layer == EAGLE_HEAD_LAYER ? g.n_layers : layer;
+  if (li < 0 || li > g.n_layers) return fail(EAGLE_EINVAL, "layer %d out of range", layer);
+  LayerW& w = c->layers[li];
+  const char* s = (const char*)src;
+  switch (which) {
+    case EAGLE_W_ATTN_NORM: HIPCHK(hipMemcpyAsync(w.attn_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
+    case EAGLE_W_MLP_NORM: HIPCHK(hipMemcpyAsync(w.mlp_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
+    case EAGLE_W_Q: rc = pack_into(c, src, w.qkv, H * dh, d, 0); break;
+    case EAGLE_W_K: rc = pack_into(c, src, w.qkv, KVH * dh, d, H * dh); break;
+    case EAGLE_W_V: rc = pack_into(c, src, w.qkv, KVH * dh, d, (H + KVH) * dh); break;
+    case EAGLE_W_O: rc = pack_into(c, src, w.o, d, H * dh, 0); break;
+    case EAGLE_W_ROUTER:
+      if (!w.moe) return fail(EAGLE_EINVAL, "layer %d has no router", layer);
+      if (c->f32) HIPCHK(hipMemcpyAsync(w.router, src, (size_t)g.n_experts * d * 4, hipMemcpyDeviceToDevice, c->stream));
+      else { k_to_f32<<<64, 256, 0, c->stream>>>((const bf16_t*)src, w.router, (size_t)g.n_experts * d); LAUNCH_CHECK(); }
+      break;
+    case EAGLE_W_GATE:
+    case EAGLE_W_UP:
+      if (w.moe) for (int e = 0; e < g.n_experts && !rc; ++e) rc = pack_into(c, s + (size_t)e * F * d * c->elt, w.e_gu[e], F, d, which == EAGLE_W_UP ? Fpad : 0);
+      else rc = pack_into(c, src, w.gu, F, d, which == EAGLE_W_UP ? Fpad : 0);
+      break;
+    case EAGLE_W_DOWN:
+      if (w.moe) for (int e = 0; e < g.n_experts && !rc; ++e) rc = pack_into(c, s + (size_t)e * d * F * c->elt, w.e_dn[e], d, F, 0);
+      else rc = pack_into(c, src, w.dn, d, F, 0);
+      break;
+  }
+  if (rc) return rc;
+  c->loaded_layer[which][li] = 1;
+  return EAGLE_OK;
+}
+
+static int all_loaded(eagle_ctx* c) {
+  const eagle_config& g = c->cfg;
+  for (int w = 0; w < EAGLE_W_ATTN_NORM; ++w)
+    if (w != EAGLE_W_FC_BIAS && !c->loaded_layer[w][0]) return fail(EAGLE_ESTATE, "tensor %d was never loaded", w);
+  for (int li = 0; li <= g.n_layers; ++li)
+    for (int w = EAGLE_W_ATTN_NORM; w < EAGLE_W_COUNT; ++w) {
+      if (w == EAGLE_W_ROUTER && !c->layers[li].moe) continue;
+      if (!c->loaded_layer[w][li]) return fail(EAGLE_ESTATE, "tensor %d of layer %d was never loaded", w, li == g.n_layers ? -1 : li);
+    }
+  return EAGLE_OK;
+}
+
+// ---------------------------------------------------------------------------- launches
+template <int NWP, int NXP>
+static hipError_t launch_gemm_mt(const PackedW& w, const bf16_t* XF, float* PT, int MT, const GemmPlan& p, hipStream_t s) {
+  dim3 grid((w.NRB + 3) / 4, p.S);
+  size_t lds = (size_t)NXP * MT * p.chunk * 1024;
+  switch (MT) {
+    case 1: k_gemm<NWP, NXP, 1><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
+    case 2: k_gemm<NWP, NXP, 2><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
+    case 3: k_gemm<NWP, NXP, 3><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
+    default: k_gemm<NWP, NXP, 4><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
+  }
+  return hipGetLastError();
+}
+
+// PT <- X (XF layout, MT row tiles) times W^T.  Returns the split count through *S.
+static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S) {
+  GemmPlan p = plan_gemm(w.NRB, w.KS, c->NXP, MT);
+  if ((size_t)p.S * w.Npad * MT * 32 > c->pt_floats) return fail(EAGLE_EINVAL, "internal: partial buffer too small");
+  if (MT < 1 || MT > 4) return fail(EAGLE_EINVAL, "internal: MT out of range");
+  *S = p.S;
+  bool timed = c->prof_mode == 2;
+  if (timed) {
+    if (c->gemm_ev_used + 2 > c->gemm_ev.size()) {
+      for (int i = 0; i < 512; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
+    }
+    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used], c->stream));
+  }
+  hipError_t e = c->f32 ? launch_gemm_mt<3, 3>(w, XF, c->PT, MT, p, c->stream) : launch_gemm_mt<1, 2>(w, XF, c->PT, MT, p, c->stream);
+  if (e != hipSuccess) return fail(EAGLE_EHIP, "gemm launch failed: %s", hipGetErrorString(e));
+  if (timed) {
+    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used + 1], c->stream));
+    c->gemm_ev_used += 2;
+    c->gemm_ev_bytes.push_back((double)w.N * w.K * c->elt);
+  }
+  return EAGLE_OK;
+}
+
+static int collect_gemm_events(eagle_ctx* c) {
+  for (size_t i = 0; i + 1 < c->gemm_ev_used; i += 2) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, c->gemm_ev[i], c->gemm_ev[i + 1]));
+    c->prof.gemm_ms += ms; c->prof.gemm_launches += 1; c->prof.gemm_weight_bytes += c->gemm_ev_bytes[i / 2];
+  }
+  c->gemm_ev_used = 0; c->gemm_ev_bytes.clear();
+  return EAGLE_OK;
+}
+
+static KVCache kv_for(eagle_ctx* c, int li) {
+  KVCache kv;
+  const eagle_config& g = c->cfg;
+  bool head = li == g.n_layers;
+  char* kb = (char*)(head ? c->dkc : c->kc);
+  char* vb = (char*)(head ? c->dvc : c->vc);
+  size_t off = head ? 0 : (size_t)li * c->layer_stride * c->elt;
+  kv.k = kb + off; kv.v = vb + off;
+  kv.page_table = c->page_table; kv.pages_per_seq = c->pps; kv.page_shift = c->page_shift;
+  kv.n_kv_heads = g.n_kv_heads; kv.head_dim = g.head_dim;
+  return kv;
+}
+
+static int resnorm(eagle_ctx* c, int M, int MT, const float* h_in, const float* PT, int S, int Npad, const float* bias,
+                   const float* gain, bf16_t* XF, float* xout) {
+  k_resnorm<<<M, 256, 0, c->stream>>>(h_in, PT, S, Npad, MT * 32, bias, c->h, gain, c->cfg.rms_eps, XF, MT, c->NXP, xout, c->cfg.d_model);
+  LAUNCH_CHECK();
+  return EAGLE_OK;
+}
+
+// One decoder layer on the rows of `pass` (h and xf_d hold the residual stream and its normalised copy).
+// next_gain: the RMSNorm gain applied to the layer's output for whoever consumes it next (nullptr = none).
+static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, int t_max, int n_new, const float* next_gain, float* xout) {
+  const eagle_config& g = c->cfg;
+  LayerW& w = c->layers[li];
+  const int H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn;
+  int S = 1, rc;
+  KVCache kv = kv_for(c, li);
+  if ((rc = gemm(c, w.qkv, c->xf_d, MT, &S))) return rc;
+  {
+    dim3 grid(M, H + 2 * KVH);
+    if (c->f32) k_qkv_rope_store<float><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
+    else k_qkv_rope_store<bf16_t><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
+    LAUNCH_CHECK();
+  }
+  {
+    int n_splits = std::max(1, std::min(16, (t_max + 63) / 64));
+    int rblocks = (pass.rows_per_seq + 31) / 32;
+    dim3 grid(n_splits, H, pass.n_seq * rblocks);
+    float scale = 1.0f / std::sqrt((float)dh);
+#define ATTN(CT, DH) k_attn<CT, DH><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale)
+    if (c->f32) { if (dh == 128) ATTN(float, 128); else if (dh == 64) ATTN(float, 64); else ATTN(float, 32); }
+    else { if (dh == 128) ATTN(bf16_t, 128); else if (dh == 64) ATTN(bf16_t, 64); else ATTN(bf16_t, 32); }
+#undef ATTN
+    LAUNCH_CHECK();
+    k_attn_combine<<<M, 256, 0, c->stream>>>(c->part_o, c->part_ml, H, dh, n_splits, c->xf_att, MT, c->NXP);
+    LAUNCH_CHECK();
+  }
+  if ((rc = gemm(c, w.o, c->xf_att, MT, &S))) return rc;
+  if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.o.Npad, nullptr, w.mlp_norm, c->xf_d, nullptr))) return rc;
+  if (w.moe) return fail(EAGLE_EINVAL, "MoE layers are not implemented yet");
+  if ((rc = gemm(c, w.gu, c->xf_d, MT, &S))) return rc;
+  {
+    dim3 grid((F / 8 + 255) / 256, M);
+    k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, (F + 31) / 32 * 32, c->xf_ffn, MT, c->NXP);
+    LAUNCH_CHECK();
+  }
+  if ((rc = gemm(c, w.dn, c->xf_ffn, MT, &S))) return rc;
+  return resnorm(c, M, MT, c->h, c->PT, S, w.dn.Npad, nullptr, next_gain, c->xf_d, xout);
+}
+
+static int lm_head(eagle_ctx* c, const Pass& pass, int M, int MT, float* out, int out_kind, int only_last_row) {
+  int S, rc;
+  if ((rc = gemm(c, c->lm_head, c->xf_d, MT, &S))) return rc;
+  dim3 grid((c->cfg.vocab + 255) / 256, M);
+  k_logits<<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, c->lm_head.Npad, MT * 32, out, out_kind, c->cfg.vocab, only_last_row);
+  LAUNCH_CHECK();
+  return EAGLE_OK;
+}
+
+// Target model over the rows of `pass`: embedding -> layers -> final norm (= features) -> LM head.
+static int target_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bool want_logits, float* logits_out, int out_kind, int only_last_row) {
+  const eagle_config& g = c->cfg;
+  const int M = pass.rows_per_seq * pass.n_seq, MT = (M + 31) / 32;
+  int rc;
+  if (c->f32) k_embed<float><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, (const float*)c->embed, c->h, g.d_model, g.vocab);
+  else k_embed<bf16_t><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, (const bf16_t*)c->embed, c->h, g.d_model, g.vocab);
+  LAUNCH_CHECK();
+  if ((rc = resnorm(c, M, MT, c->h, nullptr, 0, 0, nullptr, c->layers[0].attn_norm, c->xf_d, nullptr))) return rc;
+  for (int l = 0; l < g.n_layers; ++l) {
+    bool last = l + 1 == g.n_layers;
+    if ((rc = layer_forward(c, pass, M, MT, l, t_max, n_new, last ? c->final_norm : c->layers[l + 1].attn_norm, last ? c->featbuf : nullptr))) return rc;
+  }
+  k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->featbuf, c->F, c->pend_f, c->chunk_f, g.d_model);
+  LAUNCH_CHECK();
+  if (want_logits) return lm_head(c, pass, M, MT, logits_out, out_kind, only_last_row);
+  return EAGLE_OK;
+}
+
+// Autoregression Head over the rows of `pass`: concat(feature, token embedding) -> FC -> decoder layer (-> LM head).
+static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bool want_logits) {
+  const eagle_config& g = c->cfg;
+  const int M = pass.rows_per_seq * pass.n_seq, MT = (M + 31) / 32;
+  int rc, S;
+  if (c->f32) k_fc_input<float><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
+  else k_fc_input<bf16_t><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
+  LAUNCH_CHECK();
+  if ((rc = gemm(c, c->fc, c->xf_2d, MT, &S))) return rc;
+  const float* bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;
+  if ((rc = resnorm(c, M, MT, nullptr, c->PT, S, c->fc.Npad, bias, c->layers[g.n_layers].attn_norm, c->xf_d, nullptr))) return rc;
+  if ((rc = layer_forward(c, pass, M, MT, g.n_layers, t_max, n_new, nullptr, c->featbuf))) return rc;
+  if (!want_logits) return EAGLE_OK;
+  k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->featbuf, c->node_f, c->pend_f, c->chunk_f, g.d_model);
+  LAUNCH_CHECK();
+  return lm_head(c, pass, M, MT, c->draft_logits, 0, 0);
+}
+
+// ---------------------------------------------------------------------------- sequence life cycle
+extern "C" int eagle_reset(eagle_ctx* c) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  const int B = c->cfg.max_batch;
+  HIPCHK(hipMemsetAsync(c->st.ctx_len, 0, (size_t)B * 4, c->stream));
+  HIPCHK(hipMemsetAsync(c->st.n_pend, 0, (size_t)B * 4, c->stream));
+  HIPCHK(hipMemsetAsync(c->st.n_tok, 0, (size_t)B * 4, c->stream));
+  HIPCHK(hipMemsetAsync(c->st.step_no, 0, (size_t)B * 4, c->stream));
+  HIPCHK(hipMemsetAsync(c->hint_n, 0, (size_t)B * 4, c->stream));
+  std::fill(c->h_ctx.begin(), c->h_ctx.end(), 0); std::fill(c->h_ntok.begin(), c->h_ntok.end(), 0);
+  std::fill(c->active.begin(), c->active.end(), 0); std::fill(c->head_stale.begin(), c->head_stale.end(), 0);
+  c->n_active = 0; c->phase = 0;
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_prefill(eagle_ctx* c, int32_t seq, const int32_t* prompt, int32_t n, int32_t* first_token) {
+  if (!c || !prompt) return fail(EAGLE_EINVAL, "null argument");
+  const eagle_config& g = c->cfg;
+  int rc = all_loaded(c);
+  if (rc) return rc;
+  if (seq < 0 || seq >= g.max_batch) return fail(EAGLE_EINVAL, "slot %d out of range", seq);
+  if (seq != c->n_active) return fail(EAGLE_ESTATE, "slots must be prefilled in order: next is %d", c->n_active);
+  if (n < 1) return fail(EAGLE_EINVAL, "empty prompt");
+  if (n + 1 + c->M > g.max_seq) return fail(EAGLE_ESEQ_FULL, "prompt of %d tokens leaves no room for a step (max_seq %d)", n, g.max_seq);
+  for (int i = 0; i < n; ++i)
+    if (prompt[i] < 0 || prompt[i] >= g.vocab) return fail(EAGLE_EINVAL, "prompt token %d at %d outside the vocabulary", prompt[i], i);
+  HIPCHK(hipMemcpyAsync(c->st.tokens + (size_t)seq * c->st.tok_stride, prompt, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+  int zero = 0;
+  HIPCHK(hipMemcpyAsync(c->st.ctx_len + seq, &zero, 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));   // `zero` and `prompt` are host memory of the caller
+  for (int start = 0; start < n; start += EAGLE_PREFILL_CHUNK) {
+    const int cn = std::min(EAGLE_PREFILL_CHUNK, n - start);
+    const bool last = start + cn == n;
+    Pass pt{PASS_PREFILL_T, cn, 1, seq, 0, start, cn};
+    if ((rc = target_forward(c, pt, start + cn, cn, last, c->vanilla_logits, 1, 1))) return rc;
+    if (last) {
+      k_choose<<<1, 1024, 0, c->stream>>>(c->st, seq, c->vanilla_logits, g.vocab, g.temperature, g.seed, c->pbuf, 1, n, c->D);
+      LAUNCH_CHECK();
+      HIPCHK(hipMemcpyAsync(c->pend_f + (size_t)seq * (c->D + 1) * g.d_model, c->chunk_f + (size_t)(cn - 1) * g.d_model,
+                            (size_t)g.d_model * 4, hipMemcpyDeviceToDevice, c->stream));
+    }
+    // the head's rows for this chunk: pairs (f_i, x_{i+1}); the prompt's last position stays pending
+    const int dn = last ? cn - 1 : cn;
+    if (dn > 0) {
+      Pass pd{PASS_PREFILL_D, dn, 1, seq, 0, start, dn};
+      if ((rc = head_forward(c, pd, start + dn, dn, false))) return rc;
+    }
+  }
+  int tok = 0;
+  HIPCHK(hipMemcpyAsync(&tok, c->st.tokens + (size_t)seq * c->st.tok_stride + n, 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  if (first_token) *first_token = tok;
+  c->h_ctx[seq] = n; c->h_ntok[seq] = n + 1; c->active[seq] = 1; c->head_stale[seq] = 0;
+  c->n_active = seq + 1; c->phase = 0;
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_set_hint(eagle_ctx* c, int32_t seq, const int32_t* future, int32_t n, float alpha, float bias, uint64_t seed) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(EAGLE_EINVAL, "slot %d out of range", seq);
+  if (n < 0 || n > c->st.tok_stride) return fail(EAGLE_EINVAL, "hint length %d out of range", n);
+  if (n > 0 && !future) return fail(EAGLE_EINVAL, "future is null");
+  for (int i = 0; i < n; ++i)
+    if (future[i] < 0 || future[i] >= c->cfg.vocab) return fail(EAGLE_EINVAL, "hint token outside the vocabulary");
+  unsigned long long s64 = seed;
+  if (n > 0) HIPCHK(hipMemcpyAsync(c->hint_future + (size_t)seq * c->st.tok_stride, future, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->hint_n + seq, &n, 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->hint_alpha + seq, &alpha, 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->hint_bias + seq, &bias, 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->hint_seed + seq, &s64, 8, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  return EAGLE_OK;
+}
+
+static int step_ready(eagle_ctx* c) {
+  if (c->n_active < 1) return fail(EAGLE_ESTATE, "no active sequence: call eagle_prefill first");
+  for (int s = 0; s < c->n_active; ++s) {
+    if (c->h_ctx[s] + c->M + 1 > c->cfg.max_seq) return fail(EAGLE_ESEQ_FULL, "slot %d: %d cached positions + %d tree nodes exceed max_seq %d", s, c->h_ctx[s], c->M, c->cfg.max_seq);
+  }
+  return EAGLE_OK;
+}
+static int max_ctx(eagle_ctx* c) {
+  int m = 0;
+  for (int s = 0; s < c->n_active; ++s) m = std::max(m, c->h_ctx[s]);
+  return m;
+}
+
+static int do_draft(eagle_ctx* c) {
+  int rc = step_ready(c);
+  if (rc) return rc;
+  for (int s = 0; s < c->n_active; ++s)
+    if (c->head_stale[s]) return fail(EAGLE_ESTATE, "slot %d was advanced by eagle_vanilla_step; the head's cache is stale (prefill again)", s);
+  const int B = c->n_active, D1 = c->D + 1, ctx = max_ctx(c);
+  const eagle_config& g = c->cfg;
+  Pass p1{PASS_DRAFT_PENDING, D1, B, 0, 0, 0, 0};
+  if ((rc = head_forward(c, p1, ctx + D1, D1, true))) return rc;
+  dim3 g0(1, B);
+  k_expand<<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
+  LAUNCH_CHECK();
+  for (int lev = 1; lev < c->D; ++lev) {
+    int nr = c->tree_h.n_level_rows[lev];
+    if (nr == 0) break;
+    Pass pl{PASS_DRAFT_LEVEL, nr, B, 0, lev, 0, 0};
+    if ((rc = head_forward(c, pl, ctx + c->M, c->M, true))) return rc;
+    dim3 gl(nr, B);
+    k_expand<<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
+    LAUNCH_CHECK();
+  }
+  c->phase = 1;
+  return EAGLE_OK;
+}
+
+static int do_verify(eagle_ctx* c) {
+  if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
+  Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
+  int rc = target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
+  if (rc) return rc;
+  c->phase = 2;
+  return EAGLE_OK;
+}
+
+static int do_accept(eagle_ctx* c) {
+  if (c->phase != 2) return fail(EAGLE_ESTATE, "eagle_accept needs verified logits (call eagle_verify first)");
+  const eagle_config& g = c->cfg;
+  const int B = c->n_active;
+  k_accept<<<B, 1024, 0, c->stream>>>(c->tree_d, c->st, c->L, c->draft_logits, c->tree_tok, g.vocab, g.temperature, g.seed, c->pbuf, c->qbuf, c->path, c->tok_out, c->len_out);
+  LAUNCH_CHECK();
+  dim3 grid(4, g.n_layers + 1, B);
+  KVCache kv = kv_for(c, 0);
+  if (c->f32) k_compact<float><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
+  else k_compact<bf16_t><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
+  LAUNCH_CHECK();
+  c->phase = 0;
+  return EAGLE_OK;
+}
+
+static int fetch_results(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
+  const int B = c->n_active, D1 = c->D + 1;
+  std::vector<int> len(B);
+  HIPCHK(hipMemcpyAsync(len.data(), c->len_out, (size_t)B * 4, hipMemcpyDeviceToHost, c->stream));
+  if (out_tokens) HIPCHK(hipMemcpyAsync(out_tokens, c->tok_out, (size_t)B * D1 * 4, hipMemcpyDeviceToHost, c->stream));
+  if (path) HIPCHK(hipMemcpyAsync(path, c->path, (size_t)B * D1 * 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  for (int s = 0; s < B; ++s) {
+    if (len[s] < 1 || len[s] > D1) return fail(EAGLE_EHIP, "internal: accepted length %d out of range", len[s]);
+    c->h_ctx[s] += len[s]; c->h_ntok[s] += len[s];
+    if (out_len) out_len[s] = len[s];
+  }
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_draft_tree(eagle_ctx* c, int32_t* tree_tokens) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  int rc = do_draft(c);
+  if (rc) return rc;
+  if (tree_tokens) {
+    HIPCHK(hipMemcpyAsync(tree_tokens, c->tree_tok, (size_t)c->n_active * c->M * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(hipStreamSynchronize(c->stream));
+  }
+  return EAGLE_OK;
+}
+extern "C" int eagle_verify(eagle_ctx* c) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  return do_verify(c);
+}
+extern "C" int eagle_accept(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  int rc = do_accept(c);
+  if (rc) return rc;
+  return fetch_results(c, out_tokens, out_len, path);
+}
+
+extern "C" int eagle_step(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  int rc;
+  const bool prof = c->prof_mode > 0;
+  if (prof) HIPCHK(hipEventRecord(c->ev[0], c->stream));
+  if ((rc = do_draft(c))) return rc;
+  if (prof) HIPCHK(hipEventRecord(c->ev[1], c->stream));
+  if ((rc = do_verify(c))) return rc;
+  if (prof) HIPCHK(hipEventRecord(c->ev[2], c->stream));
+  if ((rc = do_accept(c))) return rc;
+  if (prof) HIPCHK(hipEventRecord(c->ev[3], c->stream));
+  std::vector<int> ctx_before(c->h_ctx.begin(), c->h_ctx.begin() + c->n_active);
+  if ((rc = fetch_results(c, out_tokens, out_len, path))) return rc;
+  if (prof) {
+    float a, b, d;
+    HIPCHK(hipEventElapsedTime(&a, c->ev[0], c->ev[1]));
+    HIPCHK(hipEventElapsedTime(&b, c->ev[1], c->ev[2]));
+    HIPCHK(hipEventElapsedTime(&d, c->ev[2], c->ev[3]));
+    c->prof.draft_ms += a; c->prof.verify_ms += b; c->prof.accept_ms += d; c->prof.steps += 1;
+    // algorithmic bytes of this verify: every target weight once, KV read of the context, KV write + logits
+    const eagle_config& g = c->cfg;
+    double wbytes = (double)g.vocab * g.d_model * c->elt;
+    for (int l = 0; l < g.n_layers; ++l) {
+      const LayerW& w = c->layers[l];
+      wbytes += ((double)w.qkv.N * w.qkv.K + (double)w.o.N * w.o.K) * c->elt;
+      if (!w.moe) wbytes += ((double)w.gu.N * w.gu.K + (double)w.dn.N * w.dn.K) * c->elt;
+    }
+    double kvb = 0;
+    for (int s = 0; s < c->n_active; ++s)   // context read once + the tree's own rows written
+      kvb += 2.0 * g.n_layers * g.n_kv_heads * g.head_dim * c->elt * (double)(ctx_before[s] + c->M);
+    wbytes += (double)c->n_active * c->M * g.vocab * 4.0;   // logits written
+    c->prof.verify_weight_bytes += wbytes; c->prof.verify_kv_bytes += kvb;
+    if (c->prof_mode == 2 && (rc = collect_gemm_events(c))) return rc;
+  }
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_vanilla_step(eagle_ctx* c, int32_t* tokens) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  int rc = step_ready(c);
+  if (rc) return rc;
+  const eagle_config& g = c->cfg;
+  const int B = c->n_active;
+  Pass pv{PASS_VANILLA, 1, B, 0, 0, 0, 0};
+  if ((rc = target_forward(c, pv, max_ctx(c) + 1, 1, true, c->vanilla_logits, 1, 0))) return rc;
+  k_choose<<<B, 1024, 0, c->stream>>>(c->st, 0, c->vanilla_logits, g.vocab, g.temperature, g.seed, c->pbuf, 0, 0, c->D);
+  LAUNCH_CHECK();
+  std::vector<int> tk(B);
+  for (int s = 0; s < B; ++s)
+    HIPCHK(hipMemcpyAsync(&tk[s], c->st.tokens + (size_t)s * c->st.tok_stride + c->h_ntok[s], 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  for (int s = 0; s < B; ++s) {
+    c->h_ctx[s] += 1; c->h_ntok[s] += 1; c->head_stale[s] = 1;
+    if (tokens) tokens[s] = tk[s];
+  }
+  c->phase = 0;
+  if (c->prof_mode == 2) return collect_gemm_events(c);
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_generate(eagle_ctx* c, int32_t seq, const int32_t* prompt, int32_t n_prompt, int32_t max_new,
+                              int32_t* out, int32_t* n_out, float* mean_accept_len) {
+  if (!c || !out || !n_out) return fail(EAGLE_EINVAL, "null argument");
+  if (seq != 0) return fail(EAGLE_EINVAL, "eagle_generate runs a single sequence in slot 0");
+  if (max_new < 1) return fail(EAGLE_EINVAL, "max_new must be >= 1");
+  if (n_prompt + max_new + c->M + c->D + 2 > c->cfg.max_seq) return fail(EAGLE_ESEQ_FULL, "prompt + max_new + tree does not fit max_seq");
+  int rc;
+  if ((rc = eagle_reset(c))) return rc;
+  int first;
+  if ((rc = eagle_prefill(c, 0, prompt, n_prompt, &first))) return rc;
+  int produced = 0, steps = 0, emitted = 0;
+  out[produced++] = first;
+  std::vector<int> toks(c->D + 1);
+  while (produced < max_new) {
+    int len;
+    if ((rc = eagle_step(c, toks.data(), &len, nullptr))) return rc;
+    ++steps; emitted += len;
+    for (int i = 0; i < len && produced < max_new; ++i) out[produced++] = toks[i];
+  }
+  *n_out = produced;
+  if (mean_accept_len) *mean_accept_len = steps ? (float)emitted / steps : 0.f;
+  return EAGLE_OK;
+}
+
+// ---------------------------------------------------------------------------- test / bench access
+extern "C" int eagle_get_buffer(eagle_ctx* c, int32_t which, int32_t seq, void* dst, size_t cap) {
+  if (!c || !dst) return fail(EAGLE_EINVAL, "null argument");
+  const eagle_config& g = c->cfg;
+  if (seq < 0 || seq >= g.max_batch) return fail(EAGLE_EINVAL, "slot %d out of range", seq);
+  const void* src = nullptr;
+  size_t bytes = 0;
+  int state[4];
+  switch (which) {
+    case EAGLE_BUF_LOGITS: src = c->L + (size_t)seq * c->M * g.vocab; bytes = (size_t)c->M * g.vocab * 4; break;
+    case EAGLE_BUF_FEATURES: src = c->F + (size_t)seq * c->M * g.d_model; bytes = (size_t)c->M * g.d_model * 4; break;
+    case EAGLE_BUF_DRAFT_LOGITS: src = c->draft_logits + (size_t)seq * c->M * g.vocab; bytes = (size_t)c->M * g.vocab * 4; break;
+    case EAGLE_BUF_DRAFT_FEATURES: src = c->node_f + (size_t)seq * c->M * g.d_model; bytes = (size_t)c->M * g.d_model * 4; break;
+    case EAGLE_BUF_TREE_TOKENS: src = c->tree_tok + (size_t)seq * c->M; bytes = (size_t)c->M * 4; break;
+    case EAGLE_BUF_TOKENS: src = c->st.tokens + (size_t)seq * c->st.tok_stride; bytes = (size_t)c->h_ntok[seq] * 4; break;
+    case EAGLE_BUF_VANILLA_LOGITS: src = c->vanilla_logits + (size_t)seq * g.vocab; bytes = (size_t)g.vocab * 4; break;
+    case EAGLE_BUF_STATE: {
+      HIPCHK(hipStreamSynchronize(c->stream));
+      HIPCHK(hipMemcpy(&state[0], c->st.n_tok + seq, 4, hipMemcpyDeviceToHost));
+      HIPCHK(hipMemcpy(&state[1], c->st.ctx_len + seq, 4, hipMemcpyDeviceToHost));
+      HIPCHK(hipMemcpy(&state[2], c->st.n_pend + seq, 4, hipMemcpyDeviceToHost));
+      HIPCHK(hipMemcpy(&state[3], c->st.step_no + seq, 4, hipMemcpyDeviceToHost));
+      if (cap < sizeof(state)) return fail(EAGLE_EINVAL, "destination too small");
+      memcpy(dst, state, sizeof(state));
+      return EAGLE_OK;
+    }
+    default: return fail(EAGLE_EINVAL, "unknown buffer id %d", which);
+  }
+  if (cap < bytes) return fail(EAGLE_EINVAL, "destination of %zu bytes is smaller than the %zu needed", cap, bytes);
+  HIPCHK(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_get_kv_row(eagle_ctx* c, int32_t seq, int32_t layer, int32_t pos, float* k_host, float* v_host) {
+  if (!c || !k_host || !v_host) return fail(EAGLE_EINVAL, "null argument");
+  const eagle_config& g = c->cfg;
+  int li = layer == EAGLE_HEAD_LAYER ? g.n_layers : layer;
+  if (seq < 0 || seq >= g.max_batch || li < 0 || li > g.n_layers || pos < 0 || pos >= g.max_seq) return fail(EAGLE_EINVAL, "index out of range");
+  const int n = g.n_kv_heads * g.head_dim;
+  float* tmp = c->featbuf;   // scratch, idle between passes
+  if ((size_t)2 * n > (size_t)c->Mmax * g.d_model) return fail(EAGLE_EINVAL, "internal: scratch too small");
+  KVCache kv = kv_for(c, li);
+  if (c->f32) k_read_kv_row<float><<<4, 256, 0, c->stream>>>(kv, seq, pos, tmp, tmp + n);
+  else k_read_kv_row<bf16_t><<<4, 256, 0, c->stream>>>(kv, seq, pos, tmp, tmp + n);
+  LAUNCH_CHECK();
+  HIPCHK(hipMemcpyAsync(k_host, tmp, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipMemcpyAsync(v_host, tmp + n, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_set_profiling(eagle_ctx* c, int32_t mode) {
+  if (!c || mode < 0 || mode > 2) return fail(EAGLE_EINVAL, "mode must be 0, 1 or 2");
+  c->prof_mode = mode;
+  return EAGLE_OK;
+}
+extern "C" int eagle_get_profile(eagle_ctx* c, eagle_profile* out, int32_t reset) {
+  if (!c || !out) return fail(EAGLE_EINVAL, "null argument");
+  *out = c->prof;
+  if (reset) memset(&c->prof, 0, sizeof(c->prof));
+  return EAGLE_OK;
+}

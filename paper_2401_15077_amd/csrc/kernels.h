@@ -1,0 +1,890 @@
+// Device kernels of libeagle (gfx950).  One speculative step = drafting (Sec. 3.1, App. A.1 of the paper),
+// tree-masked verification (Sec. 3.3) and acceptance (Sec. 2, App. A.2 Alg. 1) + commit.
+#pragma once
+#include "common.h"
+
+// ============================================================================ device-side model state
+struct TreeDev {
+  int M, D;
+  int parent[EAGLE_MAX_NODES], depth[EAGLE_MAX_NODES], nchild[EAGLE_MAX_NODES];
+  int child[EAGLE_MAX_NODES][EAGLE_MAX_CHILD];           // children in rank order
+  unsigned long long anc[EAGLE_MAX_NODES];               // bit u set <=> u is v or an ancestor of v
+  int n_level_rows[EAGLE_MAX_DEPTH + 1];                 // level d: depth-d nodes that have children
+  int level_rows[EAGLE_MAX_DEPTH + 1][EAGLE_MAX_NODES];
+};
+
+struct SeqState {          // all device pointers, one entry per sequence slot
+  int* ctx_len;            // positions held by the target KV cache
+  int* n_pend;             // target features waiting for the head's first pass (1..D+1)
+  int* n_tok;              // committed tokens (= ctx_len + 1 between steps)
+  int* step_no;            // draw counter for the generator
+  int* commit_base;        // ctx_len before the last commit (read by the compaction kernel)
+  int* tokens;             // [max_batch][tok_stride]
+  int tok_stride;
+};
+
+enum { PASS_VERIFY = 0, PASS_VANILLA, PASS_DRAFT_PENDING, PASS_DRAFT_LEVEL, PASS_PREFILL_T, PASS_PREFILL_D };
+struct Pass {
+  int kind, rows_per_seq, n_seq, seq0, level, chunk_start, chunk_n;
+};
+struct RowInfo {
+  int seq, valid, pos, slot, base, rel, node, causal;
+  unsigned long long mask;
+};
+
+__device__ inline RowInfo row_info(const Pass& p, const TreeDev* t, const SeqState& st, int r) {
+  RowInfo o;
+  int i = r % p.rows_per_seq;
+  o.seq = p.seq0 + r / p.rows_per_seq;
+  o.valid = 1; o.causal = 0; o.node = -1; o.mask = 0;
+  int ctx = st.ctx_len[o.seq];
+  switch (p.kind) {
+    case PASS_VERIFY:
+      o.node = i; o.base = ctx; o.rel = i; o.pos = ctx + t->depth[i]; o.slot = ctx + i; o.mask = t->anc[i];
+      break;
+    case PASS_VANILLA:
+      o.base = ctx; o.rel = 0; o.pos = ctx; o.slot = ctx; o.mask = 1ull;
+      break;
+    case PASS_DRAFT_PENDING: {
+      int np = st.n_pend[o.seq];
+      o.valid = i < np;
+      o.base = ctx - np; o.rel = o.valid ? i : 0; o.pos = o.base + o.rel; o.slot = o.pos; o.causal = 1;
+      o.node = (i == np - 1) ? 0 : -1;
+      break;
+    }
+    case PASS_DRAFT_LEVEL: {
+      int v = t->level_rows[p.level][i];
+      o.node = v; o.base = ctx - 1; o.rel = v; o.pos = ctx - 1 + t->depth[v]; o.slot = ctx - 1 + v; o.mask = t->anc[v];
+      break;
+    }
+    default:  // PASS_PREFILL_T / PASS_PREFILL_D
+      o.valid = i < p.chunk_n;
+      o.base = p.chunk_start; o.rel = o.valid ? i : 0; o.pos = o.base + o.rel; o.slot = o.pos; o.causal = 1;
+      break;
+  }
+  return o;
+}
+
+struct KVCache {
+  void* k; void* v;              // this layer's pages: [phys_page][kv_head][slot_in_page][head_dim]
+  const int* page_table;         // [max_batch][pages_per_seq] -> physical page
+  int pages_per_seq, page_shift, n_kv_heads, head_dim;
+};
+__device__ inline size_t kv_offset(const KVCache& c, int seq, int pos, int kvh) {
+  int phys = c.page_table[seq * c.pages_per_seq + (pos >> c.page_shift)];
+  return (((size_t)phys * c.n_kv_heads + kvh) << c.page_shift | (size_t)(pos & ((1 << c.page_shift) - 1))) * c.head_dim;
+}
+
+__device__ inline float cache_load(const float* p) { return *p; }
+__device__ inline float cache_load(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ inline void cache_store(float* p, float v) { *p = v; }
+__device__ inline void cache_store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ============================================================================ block reductions
+__device__ inline float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over the block in a fixed order (wave partials added in wave order): deterministic.
+__device__ inline float block_sum(float v, float* sh /*>= 16 floats*/) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += sh[i];
+  return t;
+}
+__device__ inline float block_max(float v, float* sh) {
+  v = wave_max(v);
+  int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  float t = sh[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, sh[i]);
+  return t;
+}
+// (value, index) with the larger value winning and, on equal values, the LOWER index.
+__device__ inline void better(float& v, int& i, float v2, int i2) {
+  if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
+}
+__device__ inline void block_argmax(float& v, int& i, float* shv, int* shi) {
+  for (int o = 32; o > 0; o >>= 1) {
+    float v2 = __shfl_xor(v, o, 64);
+    int i2 = __shfl_xor(i, o, 64);
+    better(v, i, v2, i2);
+  }
+  int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { shv[w] = v; shi[w] = i; }
+  __syncthreads();
+  v = shv[0]; i = shi[0];
+  for (int k = 1; k < nw; ++k) better(v, i, shv[k], shi[k]);
+}
+
+// ============================================================================ weight packing
+// src: row-major [N][K] (float or bf16).  dst: nplanes packed planes (see wpack_index), rows
+// [row_offset, row_offset+N) of a matrix with KS k-steps; plane p starts at dst + p*plane_stride.
+// One thread builds one 16-byte lane chunk (8 elements along k) of every plane.
+template <typename SrcT>
+__global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ src, bf16_t* __restrict__ dst, int N, int K,
+                                                     int row_offset, int KS, int nplanes, size_t plane_stride) {
+  size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int nrb = (N + 31) >> 5;
+  size_t total = (size_t)nrb * KS * 64;
+  if (gid >= total) return;
+  int lane = gid & 63;
+  size_t tile = gid >> 6;
+  int ks = tile % KS;
+  int rb = tile / KS;
+  int n = rb * 32 + (lane & 31);
+  int k0 = ks * 16 + (lane >> 5) * 8;
+  bf16_t out[3][8];
+  for (int t = 0; t < 8; ++t) {
+    float x = 0.f;
+    if (n < N && k0 + t < K) {
+      if constexpr (sizeof(SrcT) == 4) x = ((const float*)src)[(size_t)n * K + k0 + t];
+      else x = bf16_to_f32(((const bf16_t*)src)[(size_t)n * K + k0 + t]);
+    }
+    bf16_t p[3];
+    split_bf16(x, p, nplanes);
+    for (int q = 0; q < nplanes; ++q) out[q][t] = p[q];
+  }
+  size_t o = wpack_index(row_offset + n, k0, KS);       // row_offset is a multiple of 32
+  for (int q = 0; q < nplanes; ++q) {
+    u32x4 v;
+    v.x = out[q][0] | ((uint32_t)out[q][1] << 16); v.y = out[q][2] | ((uint32_t)out[q][3] << 16);
+    v.z = out[q][4] | ((uint32_t)out[q][5] << 16); v.w = out[q][6] | ((uint32_t)out[q][7] << 16);
+    *(u32x4*)(dst + q * plane_stride + o) = v;
+  }
+}
+
+// ============================================================================ skinny weight-streaming GEMM
+// PT[s][n][m] = sum over the split's k range of W[n][k] * X[m][k];  W packed (NWP bf16 planes), X in XF layout
+// (NXP bf16 planes, MT 32-row tiles).  A block is 4 waves; wave w owns row-block blockIdx.x*4+w (32 rows of W)
+// and streams it once: every tile is one coalesced 1 KiB load that goes straight into the MFMA A operand.  The
+// block's X slice is staged in LDS (already in B-operand order).  Products kept: plane pairs (p, q) with
+// p + q < max(NWP, NXP); pieces beyond that are below fp32 resolution of the sum.
+template <int NWP, int NXP, int MT>
+__global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, size_t w_plane_stride,
+                                              const bf16_t* __restrict__ XF, float* __restrict__ PT, int NRB, int KS,
+                                              int ks_per_split, int chunk /*k-steps per LDS stage*/, int Npad) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* xs = (u32x4*)smem;                                  // [NXP*MT][chunk][64] 16-byte lane chunks
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rb = blockIdx.x * 4 + wave;
+  const int s = blockIdx.y;
+  const int k_begin = s * ks_per_split;
+  const int k_end = min(KS, k_begin + ks_per_split);
+  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+  f32x16 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+
+  for (int c0 = k_begin; c0 < k_end; c0 += chunk) {
+    const int nk = min(chunk, k_end - c0);
+    __syncthreads();
+    // stage X: for every (plane, mt) a contiguous run of nk tiles
+    for (int pm = 0; pm < NXP * MT; ++pm) {
+      const u32x4* src = (const u32x4*)(XF + ((size_t)pm * KS + c0) * 512);
+      u32x4* dst = xs + (size_t)pm * chunk * 64;
+      for (int i = threadIdx.x; i < nk * 64; i += 256) dst[i] = src[i];
+    }
+    __syncthreads();
+    if (rb < NRB) {
+      const u32x4* wsrc = (const u32x4*)(Wp + ((size_t)rb * KS + c0) * 512) + lane;
+      constexpr int U = (NWP == 1) ? 8 : 2;
+      for (int k0 = 0; k0 < nk; k0 += U) {
+        u32x4 a[U][NWP];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int p = 0; p < NWP; ++p)
+            if (k0 + u < nk) a[u][p] = *(const u32x4*)((const bf16_t*)(wsrc + (size_t)(k0 + u) * 64) + p * w_plane_stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (k0 + u < nk) {
+#pragma unroll
+            for (int q = 0; q < NXP; ++q)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                u32x4 b = xs[((size_t)(q * MT + mt) * chunk + (k0 + u)) * 64 + lane];
+#pragma unroll
+                for (int p = 0; p < NWP; ++p)
+                  if (p + q < PMAX)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][p]),
+                                                                      __builtin_bit_cast(bf16x8, b), acc[mt], 0, 0, 0);
+              }
+          }
+        }
+      }
+    }
+  }
+  if (rb < NRB) {
+    // accumulator register r of lane l holds W-row 8*(r/4) + 4*(l/32) + r%4, X-row l%32
+    float* out = PT + ((size_t)s * Npad + (size_t)rb * 32) * (MT * 32);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int n = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        out[(size_t)n * (MT * 32) + mt * 32 + (lane & 31)] = acc[mt][r];
+      }
+  }
+}
+
+// ============================================================================ row producers
+// h[r][:] = embedding of row r's token (fp32).  EmbT = float or bf16_t.
+template <typename EmbT>
+__global__ __launch_bounds__(256) void k_embed(Pass pass, const TreeDev* tree, SeqState st, const int* tree_tok,
+                                               const EmbT* __restrict__ embed, float* __restrict__ h, int d, int vocab) {
+  int r = blockIdx.x;
+  RowInfo ri = row_info(pass, tree, st, r);
+  int tok = 0;
+  if (ri.valid) {
+    if (pass.kind == PASS_VERIFY) tok = tree_tok[ri.seq * tree->M + ri.node];
+    else tok = st.tokens[(size_t)ri.seq * st.tok_stride + ri.pos];
+  }
+  tok = min(max(tok, 0), vocab - 1);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    float v;
+    if constexpr (sizeof(EmbT) == 4) v = ((const float*)embed)[(size_t)tok * d + k];
+    else v = bf16_to_f32(((const bf16_t*)embed)[(size_t)tok * d + k]);
+    h[(size_t)r * d + k] = ri.valid ? v : 0.f;
+  }
+}
+
+__device__ inline void xf_store8(bf16_t* XF, int m, int k8, int MT, int KS, int nplanes, const float* x) {
+  bf16_t pl[3][8];
+  for (int t = 0; t < 8; ++t) {
+    bf16_t p[3];
+    split_bf16(x[t], p, nplanes);
+    for (int q = 0; q < nplanes; ++q) pl[q][t] = p[q];
+  }
+  for (int q = 0; q < nplanes; ++q) {
+    u32x4 v;
+    v.x = pl[q][0] | ((uint32_t)pl[q][1] << 16); v.y = pl[q][2] | ((uint32_t)pl[q][3] << 16);
+    v.z = pl[q][4] | ((uint32_t)pl[q][5] << 16); v.w = pl[q][6] | ((uint32_t)pl[q][7] << 16);
+    *(u32x4*)(XF + xf_index(m, k8, q, MT, KS)) = v;
+  }
+}
+
+// Input of the head's FC layer: concat(feature, embedding of the token one step ahead)  (Sec. 3.1).
+//   pending pass : feature = target feature kept at the last commit, token = committed token at pos+1
+//   level pass   : feature = the head's output at the node's parent, token = the node's drafted token
+//   draft prefill: feature = target feature of the prompt position, token = the next prompt token
+template <typename EmbT>
+__global__ __launch_bounds__(256) void k_fc_input(Pass pass, const TreeDev* tree, SeqState st, const int* tree_tok,
+                                                  const float* pend_f /*[seq][D+1][d]*/, const float* node_f /*[seq][M][d]*/,
+                                                  const float* chunk_f /*[chunk][d]*/, const EmbT* __restrict__ embed,
+                                                  bf16_t* XF, int d, int vocab, int MT, int nplanes) {
+  int r = blockIdx.x;
+  RowInfo ri = row_info(pass, tree, st, r);
+  const int KS = 2 * d / 16;
+  const float* f = nullptr;
+  int tok = 0;
+  if (ri.valid) {
+    if (pass.kind == PASS_DRAFT_PENDING) {
+      f = pend_f + ((size_t)ri.seq * (tree->D + 1) + ri.rel) * d;
+      tok = st.tokens[(size_t)ri.seq * st.tok_stride + ri.pos + 1];
+    } else if (pass.kind == PASS_DRAFT_LEVEL) {
+      f = node_f + ((size_t)ri.seq * tree->M + tree->parent[ri.node]) * d;
+      tok = tree_tok[ri.seq * tree->M + ri.node];
+    } else {
+      f = chunk_f + (size_t)ri.rel * d;
+      tok = st.tokens[(size_t)ri.seq * st.tok_stride + ri.pos + 1];
+    }
+  }
+  tok = min(max(tok, 0), vocab - 1);
+  for (int k8 = threadIdx.x * 8; k8 < 2 * d; k8 += blockDim.x * 8) {
+    float x[8];
+    for (int t = 0; t < 8; ++t) {
+      int k = k8 + t;
+      float v = 0.f;
+      if (ri.valid) {
+        if (k < d) v = f[k];
+        else if constexpr (sizeof(EmbT) == 4) v = ((const float*)embed)[(size_t)tok * d + (k - d)];
+        else v = bf16_to_f32(((const bf16_t*)embed)[(size_t)tok * d + (k - d)]);
+      }
+      x[t] = v;
+    }
+    xf_store8(XF, r, k8, MT, KS, nplanes, x);
+  }
+}
+
+// h_out[r] = h_in[r] + sum_s PT[s][:, r] + bias ;  x = gain ? rmsnorm(h_out[r]) * gain : h_out[r]
+// x goes out in XF layout (GEMM input) and, optionally, as fp32 rows (features).  One block per row.
+__global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float* __restrict__ PT, int S, int Npad, int Mpad,
+                                                 const float* bias, float* h_out, const float* gain, float eps,
+                                                 bf16_t* XF, int MT, int nplanes, float* xout, int d) {
+  __shared__ float sh[16];
+  int r = blockIdx.x;
+  float ss = 0.f;
+  // each thread owns chunks of 8 consecutive k
+  for (int k8 = threadIdx.x * 8; k8 < d; k8 += blockDim.x * 8) {
+    for (int t = 0; t < 8; ++t) {
+      int k = k8 + t;
+      float v = h_in ? h_in[(size_t)r * d + k] : 0.f;
+      if (PT) {
+        float a = 0.f;
+        for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + k) * Mpad + r];
+        v += a;
+      }
+      if (bias) v += bias[k];
+      h_out[(size_t)r * d + k] = v;
+      ss += v * v;
+    }
+  }
+  ss = block_sum(ss, sh);
+  float rstd = gain ? 1.0f / sqrtf(ss / (float)d + eps) : 1.0f;
+  const int KS = d / 16;
+  for (int k8 = threadIdx.x * 8; k8 < d; k8 += blockDim.x * 8) {
+    float x[8];
+    for (int t = 0; t < 8; ++t) {
+      float v = h_out[(size_t)r * d + k8 + t];
+      x[t] = gain ? v * rstd * gain[k8 + t] : v;
+      if (xout) xout[(size_t)r * d + k8 + t] = x[t];
+    }
+    if (XF) xf_store8(XF, r, k8, MT, KS, nplanes, x);
+  }
+}
+
+// q, k, v = rows of PT (the fused QKV projection); rotate-half RoPE on q and k with the row's position id;
+// q -> Q[r][head][dh] fp32, k and v -> this layer's paged cache at the row's slot.  Block = one (row, head).
+template <typename CT>
+__global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev* tree, SeqState st,
+                                                       const float* __restrict__ PT, int S, int Npad, int Mpad,
+                                                       const float* __restrict__ rope_cos, const float* __restrict__ rope_sin,
+                                                       float* Q, KVCache kv, int H) {
+  int r = blockIdx.x, hd = blockIdx.y;
+  RowInfo ri = row_info(pass, tree, st, r);
+  const int dh = kv.head_dim, half = dh >> 1, KVH = kv.n_kv_heads;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    int n1 = hd * dh + i, n2 = n1 + half;
+    float a = 0.f, b = 0.f;
+    for (int s = 0; s < S; ++s) {
+      a += PT[((size_t)s * Npad + n1) * Mpad + r];
+      b += PT[((size_t)s * Npad + n2) * Mpad + r];
+    }
+    if (hd < H + KVH) {   // q or k head: rotate
+      float c = rope_cos[(size_t)ri.pos * half + i], sn = rope_sin[(size_t)ri.pos * half + i];
+      float a2 = a * c - b * sn, b2 = b * c + a * sn;
+      a = a2; b = b2;
+    }
+    if (hd < H) {
+      Q[((size_t)r * H + hd) * dh + i] = a;
+      Q[((size_t)r * H + hd) * dh + i + half] = b;
+    } else if (ri.valid) {
+      int kvh = (hd - H) % KVH;
+      CT* base = (CT*)(hd < H + KVH ? kv.k : kv.v) + kv_offset(kv, ri.seq, ri.slot, kvh);
+      cache_store(base + i, a);
+      cache_store(base + i + half, b);
+    }
+  }
+}
+
+// ============================================================================ tree-masked paged attention
+// One block = (kv split, query head, sequence x 32-row block).  Keys: cache slots [0, base) are visible to every
+// row; slot base+j is visible to a row iff bit j of its ancestor mask is set (tree passes) or j <= its own
+// relative index (causal passes).  Online softmax over 64-token tiles; partial (max, sum, acc) per split.
+template <typename CT, int DH>
+__global__ __launch_bounds__(256) void k_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
+                                              const float* __restrict__ Q, float* part_o, float* part_ml, int H,
+                                              int n_splits, int n_new /*slots past base that may be visible*/, float scale) {
+  constexpr int NRG = 256 / DH;            // row groups in the PV phase
+  constexpr int RPT = 32 / NRG;            // rows per thread in the PV phase
+  __shared__ float q_s[32][DH];
+  __shared__ float s_s[32][64];
+  __shared__ float alpha_s[32], m_s[32], l_s[32];
+  __shared__ int rel_s[32], causal_s[32];
+  __shared__ unsigned long long mask_s[32];
+  const int split = blockIdx.x, hd = blockIdx.y;
+  const int rblocks = (pass.rows_per_seq + 31) / 32;
+  const int seq_l = blockIdx.z / rblocks, rblk = blockIdx.z % rblocks;
+  const int r0 = seq_l * pass.rows_per_seq + rblk * 32;
+  const int R = min(32, pass.rows_per_seq - rblk * 32);
+  const int kvh = hd / (H / kv.n_kv_heads);
+  const int tid = threadIdx.x;
+  RowInfo r_first = row_info(pass, tree, st, r0);
+  const int seq = r_first.seq, base = r_first.base;
+  if (tid < 32) {
+    if (tid < R) {
+      RowInfo ri = row_info(pass, tree, st, r0 + tid);
+      rel_s[tid] = ri.rel; causal_s[tid] = ri.causal; mask_s[tid] = ri.mask;
+    }
+    m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f;
+  }
+  for (int i = tid; i < R * DH; i += 256) q_s[i / DH][i % DH] = Q[((size_t)(r0 + i / DH) * H + hd) * DH + i % DH];
+  const int T = base + n_new;
+  const int tps = ((T + n_splits - 1) / n_splits + 63) / 64 * 64;
+  const int t_begin = split * tps, t_end = min(T, t_begin + tps);
+  float acc[RPT];
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
+  const int d_own = tid % DH, rg = tid / DH;
+  __syncthreads();
+  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+    // ---- scores: thread = (token tl, row quarter rq)
+    {
+      const int tl = tid & 63, rq = tid >> 6;
+      const int t = t0 + tl;
+      if (t < t_end) {
+        const CT* kp = (const CT*)kv.k + kv_offset(kv, seq, t, kvh);
+        float kr[DH];
+#pragma unroll
+        for (int d = 0; d < DH; ++d) kr[d] = cache_load(kp + d);
+        for (int r = rq; r < R; r += 4) {
+          float sdot = 0.f;
+#pragma unroll
+          for (int d = 0; d < DH; ++d) sdot += q_s[r][d] * kr[d];
+          bool vis = t < base;
+          if (!vis) {
+            int j = t - base;
+            vis = causal_s[r] ? (j <= rel_s[r]) : (j < 64 && ((mask_s[r] >> j) & 1ull));
+          }
+          s_s[r][tl] = vis ? sdot * scale : -INFINITY;
+        }
+      } else {
+        for (int r = rq; r < R; r += 4) s_s[r][tl] = -INFINITY;
+      }
+    }
+    __syncthreads();
+    // ---- running max / sum: wave w handles rows w, w+4, ...; lane = token
+    {
+      const int lane = tid & 63, w = tid >> 6;
+      for (int r = w; r < R; r += 4) {
+        float sv = s_s[r][lane];
+        float mx = wave_max(sv);
+        float m_old = m_s[r];
+        float m_new = fmaxf(m_old, mx);
+        float p = (m_new == -INFINITY) ? 0.f : __expf(sv - m_new);
+        float al = (m_new == -INFINITY || m_old == -INFINITY) ? (m_old == -INFINITY ? 0.f : 1.f) : __expf(m_old - m_new);
+        float ps = wave_sum(p);
+        s_s[r][lane] = p;
+        if (lane == 0) { m_s[r] = m_new; l_s[r] = l_s[r] * al + ps; alpha_s[r] = al; }
+      }
+    }
+    __syncthreads();
+    // ---- acc = acc*alpha + P.V : thread = (d_own, row group)
+    {
+      const int nt = min(64, t_end - t0);
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        int r = rg + i * NRG;
+        if (r < R) acc[i] *= alpha_s[r];
+      }
+      for (int tl = 0; tl < nt; ++tl) {
+        const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
+        float vv = cache_load(vp + d_own);
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          int r = rg + i * NRG;
+          if (r < R) acc[i] += s_s[r][tl] * vv;
+        }
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    int r = rg + i * NRG;
+    if (r < R) part_o[(((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + d_own] = acc[i];
+  }
+  if (tid < R) {
+    size_t o = (((size_t)(r0 + tid) * H + hd) * n_splits + split) * 2;
+    part_ml[o] = m_s[tid];
+    part_ml[o + 1] = l_s[tid];
+  }
+}
+
+// Merge the splits and write the attention output as the next GEMM's input (XF layout).  Block = one row.
+__global__ __launch_bounds__(256) void k_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                      int H, int DH, int n_splits, bf16_t* XF, int MT, int nplanes) {
+  int r = blockIdx.x;
+  const int K = H * DH, KS = K / 16;
+  for (int k8 = threadIdx.x * 8; k8 < K; k8 += blockDim.x * 8) {
+    int hd = k8 / DH, d0 = k8 % DH;
+    const float* ml = part_ml + ((size_t)r * H + hd) * n_splits * 2;
+    float m = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, ml[2 * s]);
+    float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int s = 0; s < n_splits; ++s) {
+      float ms = ml[2 * s];
+      if (ms == -INFINITY) continue;
+      float w = __expf(ms - m);
+      den += w * ml[2 * s + 1];
+      const float* o = part_o + (((size_t)r * H + hd) * n_splits + s) * DH + d0;
+      for (int t = 0; t < 8; ++t) x[t] += w * o[t];
+    }
+    float inv = den > 0.f ? 1.0f / den : 0.f;
+    for (int t = 0; t < 8; ++t) x[t] *= inv;
+    xf_store8(XF, r, k8, MT, KS, nplanes, x);
+  }
+}
+
+// ============================================================================ SwiGLU and logits epilogues
+// act[r][k] = silu(gate) * up, gate = sum_s PT[s][k][r], up = sum_s PT[s][up_off + k][r]   (F = d_ffn)
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, int S, int Npad, int Mpad, int F, int up_off,
+                                                bf16_t* XF, int MT, int nplanes) {
+  int r = blockIdx.y;
+  int k8 = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (k8 >= F) return;
+  float x[8];
+  for (int t = 0; t < 8; ++t) {
+    float g = 0.f, u = 0.f;
+    for (int s = 0; s < S; ++s) {
+      g += PT[((size_t)s * Npad + k8 + t) * Mpad + r];
+      u += PT[((size_t)s * Npad + up_off + k8 + t) * Mpad + r];
+    }
+    x[t] = g / (1.0f + __expf(-g)) * u;
+  }
+  xf_store8(XF, r, k8, MT, F / 16, nplanes, x);
+}
+
+// logits[dst_row(r)][v] = sum_s PT[s][v][r].  Where a pass's row maps to no output (padding rows, pending rows
+// other than the root pair) nothing is written.  out_kind 0: per-node buffer [seq][M][V]; 1: per-seq [seq][V].
+__global__ __launch_bounds__(256) void k_logits(Pass pass, const TreeDev* tree, SeqState st, const float* __restrict__ PT,
+                                                int S, int Npad, int Mpad, float* out, int out_kind, int V, int only_last_row) {
+  int r = blockIdx.y;
+  RowInfo ri = row_info(pass, tree, st, r);
+  if (!ri.valid) return;
+  size_t dst;
+  if (out_kind == 0) {
+    if (ri.node < 0) return;
+    dst = ((size_t)ri.seq * tree->M + ri.node) * V;
+  } else {
+    if (only_last_row && ri.rel != pass.chunk_n - 1 && pass.kind != PASS_VANILLA) return;
+    dst = (size_t)ri.seq * V;
+  }
+  int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= V) return;
+  float a = 0.f;
+  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + v) * Mpad + r];
+  out[dst + v] = a;
+}
+
+// copy rows (features): dst[dst_row(r)] = src[r]
+__global__ __launch_bounds__(256) void k_store_rows(Pass pass, const TreeDev* tree, SeqState st, const float* src,
+                                                    float* node_dst /*[seq][M][d]*/, float* pend_dst /*[seq][D+1][d]*/,
+                                                    float* chunk_dst /*[chunk][d]*/, int d) {
+  int r = blockIdx.x;
+  RowInfo ri = row_info(pass, tree, st, r);
+  if (!ri.valid) return;
+  float* dst = nullptr;
+  if (pass.kind == PASS_VERIFY || pass.kind == PASS_DRAFT_LEVEL) dst = node_dst + ((size_t)ri.seq * tree->M + ri.node) * d;
+  else if (pass.kind == PASS_DRAFT_PENDING) { if (ri.node == 0) dst = node_dst + ((size_t)ri.seq * tree->M) * d; }
+  else if (pass.kind == PASS_PREFILL_T) {
+    dst = chunk_dst + (size_t)ri.rel * d;
+  } else if (pass.kind == PASS_VANILLA) dst = pend_dst + (size_t)ri.seq * (tree->D + 1) * d;
+  if (!dst) return;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = src[(size_t)r * d + k];
+}
+
+// ============================================================================ token choice
+struct HintDev {
+  const int* future;     // [max_batch][stride]
+  int stride;
+  const int* n;          // [max_batch] tokens known (0 = off)
+  const float* alpha;    // [max_batch]
+  const float* bias;
+  const unsigned long long* seed;
+};
+
+// Children of one tree node = the top-k entries of its (knob-adjusted, Gumbel-perturbed when non-greedy) head
+// logits, rank r = (r+1)-th largest, equal scores -> lower token id (App. A.1).  Block = (parent row, seq).
+__global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_seq, const TreeDev* tree, SeqState st,
+                                                 float* draft_logits /*[seq][M][V]*/, int* tree_tok, int* on_path, HintDev hint,
+                                                 int V, float temperature, unsigned long long rng_seed, float* scratch /*[seq][rows][V]*/) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ int chosen[EAGLE_MAX_CHILD];
+  const int seq = blockIdx.y;
+  const int v = level < 0 ? 0 : tree->level_rows[level][blockIdx.x];
+  const int M = tree->M;
+  float* lg = draft_logits + ((size_t)seq * M + v) * V;
+  const int n = st.n_tok[seq];
+  if (v == 0 && threadIdx.x == 0) {
+    tree_tok[seq * M] = st.tokens[(size_t)seq * st.tok_stride + n - 1];
+    int hn = hint.n[seq];
+    on_path[seq * M] = (hn > n - 1) && hint.future[(size_t)seq * hint.stride + n - 1] == tree_tok[seq * M];
+  }
+  __syncthreads();
+  // acceptance knob of the synthetic workload
+  const int pos_child = n + tree->depth[v];
+  int hinted = -1;
+  if (on_path[seq * M + v] && pos_child < hint.n[seq]) {
+    hinted = hint.future[(size_t)seq * hint.stride + pos_child];
+    if (threadIdx.x == 0) {
+      uint32_t k24 = rng_u24(rng_prefix(hint.seed[seq], PURPOSE_HINT, 0), (uint32_t)seq, 0, (uint32_t)pos_child);
+      bool hit = (float)k24 * 5.9604644775390625e-8f < hint.alpha[seq];
+      lg[hinted] += hit ? hint.bias[seq] : -hint.bias[seq];
+    }
+  }
+  __syncthreads();
+  const int nk = tree->nchild[v];
+  const float* score = lg;
+  if (temperature > 0.f) {
+    float* sc = scratch + ((size_t)seq * gridDim.x + blockIdx.x) * V;
+    unsigned long long pre = rng_prefix(rng_seed, PURPOSE_GUMBEL, (unsigned long long)st.step_no[seq]);
+    for (int j = threadIdx.x; j < V; j += blockDim.x) {
+      float u = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)j) + 0.5f) * 5.9604644775390625e-8f;
+      sc[j] = lg[j] / temperature - logf(-logf(u));
+    }
+    score = sc;
+    __syncthreads();
+  }
+  for (int r = 0; r < nk; ++r) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += blockDim.x) {
+      bool taken = false;
+      for (int q = 0; q < r; ++q) taken |= (chosen[q] == j);
+      if (!taken) better(bv, bi, score[j], j);
+    }
+    block_argmax(bv, bi, shv, shi);
+    if (threadIdx.x == 0) {
+      chosen[r] = bi;
+      int c = tree->child[v][r];
+      tree_tok[seq * M + c] = bi;
+      on_path[seq * M + c] = (hinted >= 0 && bi == hinted);
+    }
+    __syncthreads();
+  }
+}
+
+// softmax(x / T) over V entries into p (block-wide), returns nothing; sh >= 16 floats
+__device__ inline void block_softmax(const float* x, float* p, int V, float invT, float* sh) {
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < V; j += blockDim.x) mx = fmaxf(mx, x[j] * invT);
+  mx = block_max(mx, sh);
+  float sm = 0.f;
+  for (int j = threadIdx.x; j < V; j += blockDim.x) { float e = expf(x[j] * invT - mx); p[j] = e; sm += e; }
+  sm = block_sum(sm, sh);
+  for (int j = threadIdx.x; j < V; j += blockDim.x) p[j] = p[j] / sm;
+  __syncthreads();
+}
+
+// smallest x with cumsum(p)[x] > u * sum(p); block-wide, result broadcast through *res (shared)
+__device__ inline int block_inverse_cdf(const float* p, int V, float u, float* sh_f /*>= blockDim.x*/, int* res) {
+  const int nt = blockDim.x;
+  const int per = (V + nt - 1) / nt;
+  const int j0 = threadIdx.x * per, j1 = min(V, j0 + per);
+  float s = 0.f;
+  for (int j = j0; j < j1; ++j) s += p[j];
+  sh_f[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+    for (int i = 0; i < nt; ++i) { float t = sh_f[i]; sh_f[i] = tot; tot += t; }   // exclusive prefix, fixed order
+    sh_f[nt] = tot;
+    *res = V - 1;
+  }
+  __syncthreads();
+  const float target = u * sh_f[nt];
+  float c = sh_f[threadIdx.x];
+  float nxt = threadIdx.x + 1 < nt ? sh_f[threadIdx.x + 1] : sh_f[nt];
+  __syncthreads();
+  if (j0 < j1 && c <= target && (target < nxt || threadIdx.x + 1 == nt || j1 == V)) {
+    int found = -1, last_pos = -1;
+    for (int j = j0; j < j1; ++j) {
+      if (p[j] > 0.f) last_pos = j;
+      c += p[j];
+      if (c > target) { found = j; break; }
+    }
+    if (found < 0) found = last_pos;            // rounding left the running sum just short of the target
+    if (found >= 0) atomicMin(res, found);
+  }
+  __syncthreads();
+  return *res;
+}
+
+// Pick the next token of every sequence from logits[seq][V] (prefill's first token, vanilla decoding):
+// argmax when greedy, else one inverse-CDF draw from softmax(logits / T).  Also advances the sequence state.
+__global__ __launch_bounds__(1024) void k_choose(SeqState st, int seq0, const float* logits, int V, float temperature,
+                                                 unsigned long long rng_seed, float* pbuf /*[seq][V]*/, int is_prefill,
+                                                 int prefill_n, int max_pend) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ float sh_f[1025];
+  __shared__ int res;
+  const int seq = seq0 + blockIdx.x;
+  const float* lg = logits + (size_t)seq * V;
+  int tok;
+  if (temperature <= 0.f) {
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += blockDim.x) better(bv, bi, lg[j], j);
+    block_argmax(bv, bi, shv, shi);
+    tok = bi;
+  } else {
+    float* p = pbuf + (size_t)seq * V;
+    block_softmax(lg, p, V, 1.0f / temperature, shv);
+    int step = is_prefill ? 0 : st.step_no[seq];
+    float u = (float)rng_u24(rng_prefix(rng_seed, PURPOSE_FINAL, (unsigned long long)step), (uint32_t)seq, 0, 0) * 5.9604644775390625e-8f;
+    tok = block_inverse_cdf(p, V, u, sh_f, &res);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (is_prefill) {
+      st.tokens[(size_t)seq * st.tok_stride + prefill_n] = tok;
+      st.n_tok[seq] = prefill_n + 1; st.ctx_len[seq] = prefill_n; st.n_pend[seq] = 1; st.step_no[seq] = 1;
+    } else {
+      int n = st.n_tok[seq];
+      st.tokens[(size_t)seq * st.tok_stride + n] = tok;
+      st.n_tok[seq] = n + 1; st.ctx_len[seq] += 1; st.n_pend[seq] = max_pend + 1 /* head is stale after vanilla */;
+      st.step_no[seq] += 1;
+    }
+  }
+}
+
+// Acceptance (Sec. 2; App. A.2, Alg. 1 applied recursively at every node).  Block = one sequence.
+//   greedy : follow the child whose token equals argmax of the target logits at the current node
+//   T > 0  : children in rank order, accept child i when r * q_i(t_i) < p(t_i); on rejection
+//            p <- norm(max(0, p - q_i)) and q_{i+1} = q_i without t_i, renormalised (children were drawn
+//            without replacement); when nothing is accepted draw the bonus token from what is left of p.
+__global__ __launch_bounds__(1024) void k_accept(const TreeDev* tree, SeqState st, const float* L /*[seq][M][V]*/,
+                                                 const float* draft_logits, const int* tree_tok, int V, float temperature,
+                                                 unsigned long long rng_seed, float* pbuf, float* qbuf,
+                                                 int* path_out /*[seq][D+1]*/, int* tok_out, int* len_out) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  __shared__ float sh_f[1025];
+  __shared__ int res, s_next;
+  const int seq = blockIdx.x, M = tree->M, D1 = tree->D + 1;
+  int cur = 0, len = 1, bonus = 0;
+  if (threadIdx.x == 0) path_out[seq * D1] = 0;
+  const int step = st.step_no[seq];
+  while (true) {
+    const float* lg = L + ((size_t)seq * M + cur) * V;
+    const int nk = tree->nchild[cur];
+    if (temperature <= 0.f) {
+      float bv = -INFINITY; int bi = 0x7fffffff;
+      for (int j = threadIdx.x; j < V; j += blockDim.x) better(bv, bi, lg[j], j);
+      block_argmax(bv, bi, shv, shi);
+      if (threadIdx.x == 0) {
+        s_next = -1;
+        for (int r = 0; r < nk; ++r) {
+          int c = tree->child[cur][r];
+          if (tree_tok[seq * M + c] == bi) { s_next = c; break; }
+        }
+      }
+      __syncthreads();
+      if (s_next < 0) { bonus = bi; break; }
+    } else {
+      float* p = pbuf + (size_t)seq * V;
+      float* q = qbuf + (size_t)seq * V;
+      const float invT = 1.0f / temperature;
+      block_softmax(lg, p, V, invT, shv);
+      if (nk > 0) block_softmax(draft_logits + ((size_t)seq * M + cur) * V, q, V, invT, shv);
+      if (threadIdx.x == 0) s_next = -1;
+      __syncthreads();
+      for (int r = 0; r < nk; ++r) {
+        const int c = tree->child[cur][r];
+        const int t = tree_tok[seq * M + c];
+        float rr = (float)rng_u24(rng_prefix(rng_seed, PURPOSE_ACCEPT, (unsigned long long)step), (uint32_t)seq, (uint32_t)c, 0) * 5.9604644775390625e-8f;
+        bool ok = rr * q[t] < p[t];
+        __syncthreads();
+        if (ok) { if (threadIdx.x == 0) s_next = c; break; }
+        // residual target, proposal without t
+        float sm = 0.f;
+        for (int j = threadIdx.x; j < V; j += blockDim.x) { float d = fmaxf(p[j] - q[j], 0.f); sm += d; }
+        sm = block_sum(sm, shv);
+        if (sm > 1e-20f)
+          for (int j = threadIdx.x; j < V; j += blockDim.x) p[j] = fmaxf(p[j] - q[j], 0.f) / sm;
+        __syncthreads();
+        if (threadIdx.x == 0) q[t] = 0.f;
+        __syncthreads();
+        float qs = 0.f;
+        for (int j = threadIdx.x; j < V; j += blockDim.x) qs += q[j];
+        qs = block_sum(qs, shv);
+        if (qs > 0.f)
+          for (int j = threadIdx.x; j < V; j += blockDim.x) q[j] = q[j] / qs;
+        __syncthreads();
+      }
+      __syncthreads();
+      if (s_next < 0) {
+        float u = (float)rng_u24(rng_prefix(rng_seed, PURPOSE_FINAL, (unsigned long long)step), (uint32_t)seq, (uint32_t)cur, 0) * 5.9604644775390625e-8f;
+        bonus = block_inverse_cdf(p, V, u, sh_f, &res);
+        break;
+      }
+    }
+    cur = s_next;
+    if (threadIdx.x == 0) path_out[seq * D1 + len] = cur;
+    ++len;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const int n = st.n_tok[seq];
+    for (int i = 1; i < len; ++i) {
+      int t = tree_tok[seq * M + path_out[seq * D1 + i]];
+      tok_out[seq * D1 + i - 1] = t;
+      st.tokens[(size_t)seq * st.tok_stride + n + i - 1] = t;
+    }
+    tok_out[seq * D1 + len - 1] = bonus;
+    st.tokens[(size_t)seq * st.tok_stride + n + len - 1] = bonus;
+    len_out[seq] = len;
+    st.commit_base[seq] = st.ctx_len[seq];
+    st.n_tok[seq] = n + len; st.ctx_len[seq] += len; st.n_pend[seq] = len; st.step_no[seq] = step + 1;
+  }
+}
+
+// Commit (Sec. 3.3: accepted tokens and their features are kept): for every layer, KV rows of the accepted
+// nodes move from slot base+path[i] to base+i, and the accepted nodes' target features become the pending
+// features of the next drafting phase.  ONE launch: blockIdx.y = layer (last y = the feature rows).
+// A thread owns one 16-byte column of a row and moves i = 1..len-1 in increasing order; since path[i] >= i and
+// path is increasing, a destination is never a source that is still to be read.
+template <typename CT>
+__global__ __launch_bounds__(256) void k_compact(const TreeDev* tree, SeqState st, const int* path, const int* len_p,
+                                                 void* kcache, void* vcache, size_t layer_stride_elems, int n_layers,
+                                                 KVCache kv, const float* F /*[seq][M][d]*/, float* pend_f, int d) {
+  const int seq = blockIdx.z, layer = blockIdx.y;
+  const int D1 = tree->D + 1, M = tree->M;
+  const int len = len_p[seq];
+  const int* pth = path + seq * D1;
+  if (layer == n_layers) {
+    for (int i = 0; i < len; ++i) {
+      const float* src = F + ((size_t)seq * M + pth[i]) * d;
+      float* dst = pend_f + ((size_t)seq * D1 + i) * d;
+      for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < d; k += gridDim.x * blockDim.x) dst[k] = src[k];
+    }
+    return;
+  }
+  const int base = st.commit_base[seq];
+  constexpr int EPC = 16 / sizeof(CT);                        // elements per 16-byte column
+  const int cols = kv.n_kv_heads * kv.head_dim / EPC;
+  kv.k = (CT*)kcache + (size_t)layer * layer_stride_elems;
+  kv.v = (CT*)vcache + (size_t)layer * layer_stride_elems;
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < 2 * cols; c += gridDim.x * blockDim.x) {
+    const int which = c / cols, cc = c % cols;
+    const int kvh = cc * EPC / kv.head_dim, off = cc * EPC % kv.head_dim;
+    CT* cache = (CT*)(which ? kv.v : kv.k);
+    for (int i = 1; i < len; ++i) {
+      if (pth[i] == i) continue;
+      u32x4 val = *(const u32x4*)(cache + kv_offset(kv, seq, base + pth[i], kvh) + off);
+      *(u32x4*)(cache + kv_offset(kv, seq, base + i, kvh) + off) = val;
+    }
+  }
+}
+
+// ============================================================================ debug / test access
+template <typename CT>
+__global__ void k_read_kv_row(KVCache kv, int seq, int pos, float* kout, float* vout) {
+  int n = kv.n_kv_heads * kv.head_dim;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    int kvh = i / kv.head_dim, d = i % kv.head_dim;
+    size_t o = kv_offset(kv, seq, pos, kvh) + d;
+    kout[i] = cache_load((const CT*)kv.k + o);
+    vout[i] = cache_load((const CT*)kv.v + o);
+  }
+}
+
+__global__ void k_fill_u32(uint32_t* p, uint32_t v, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}

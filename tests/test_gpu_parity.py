@@ -1,0 +1,80 @@
+"""GPU parity: the HIP path against the CPU oracle on the same seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_2401_15077_amd as pkg
+import synth
+from lockstep import Stats, check_prefill, lockstep_step
+from oracle.eagle_oracle import Oracle, u24, PURPOSE_HINT
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def make_pair(shape_name, tree, seed, *, max_seq=256, temperature=0.0, rng_seed=0, dtype=np.float64, n_layers=None):
+    s = synth.SHAPES[shape_name]
+    if n_layers is not None:
+        s = s.twin(n_layers)
+    par, rk = synth.TREES[tree]
+    eng = pkg.Eagle(s, par, rk, max_seq=max_seq, temperature=temperature, seed=rng_seed)
+    eng.load_weights(synth.iter_weights(s, seed, synth.device_fmt(s)))
+    orc = Oracle(s, synth.make_weights(s, seed, synth.oracle_fmt(s)), par, rk, max_seq=max_seq,
+                 temperature=temperature, seed=rng_seed, dtype=dtype)
+    return s, eng, orc
+
+
+def test_tiny_fp32_full_run_matches_oracle_and_vanilla():
+    """Config 1: tiny fp32 model, 32-token prompt, 64 new tokens, T15 tree, greedy; also vanilla greedy."""
+    s, eng, orc = make_pair("tiny", "T15", seed=1)
+    prompt = synth.prompt(1, 32, s.vocab)
+    print("prefill", flush=True)
+    check_prefill(eng, orc, prompt, TOL["fp32"])
+    st = Stats()
+    gen = [orc.x[-1]]
+    while len(gen) < 64:
+        gen += lockstep_step(eng, orc, st, TOL["fp32"])
+    print(f"steps={st.steps} tau={st.tau:.2f} max|dL|={st.max_logit_err:.2e} max|dF|={st.max_feat_err:.2e} "
+          f"draft {st.max_draft_logit_err:.2e}/{st.max_draft_feat_err:.2e} excused={st.excused_tree_slots}/{st.excused_accepts}", flush=True)
+    assert st.excused_accepts == 0 and st.excused_tree_slots == 0
+    assert list(eng.get_buffer(pkg.BUF_TOKENS))[:len(orc.x)] == orc.x
+    # the paper's invariant on the GPU side: speculative greedy == vanilla greedy, token for token
+    eng.reset()
+    eng.prefill(0, prompt)
+    van = [int(eng.get_buffer(pkg.BUF_TOKENS)[-1])]
+    while len(van) < 64:
+        van.append(int(eng.vanilla_step()[0]))
+    assert van == gen[:64]
+    out, tau = eng.generate(prompt, 64)
+    assert list(out) == gen[:64] and tau >= 1.0
+    eng.close()
+
+
+def test_tiny_hint_knob_accept_lengths_and_compaction():
+    """Acceptance knob: accepted lengths equal the runs of hash hits; the compacted KV rows equal the oracle's."""
+    s, eng, orc = make_pair("tiny", "T26", seed=2)
+    prompt = synth.prompt(2, 20, s.vocab)
+    par, rk = synth.TREES["T26"]
+    future = list(prompt) + Oracle(s, synth.make_weights(s, 2, "f32"), par, rk, max_seq=256).generate_vanilla(prompt, 80)
+    alpha, hseed = 0.75, 1234
+    orc.set_hint(future, alpha, 30.0, hseed)
+    check_prefill(eng, orc, prompt, TOL["fp32"])
+    eng.set_hint(0, future, alpha, 30.0, hseed)
+    st = Stats()
+    while len(orc.x) < len(prompt) + 60:
+        n = len(orc.x)
+        run = 0
+        while run < orc.tree.D and np.float32(u24(hseed, PURPOSE_HINT, 0, 0, 0, n + run) * 2.0 ** -24) < np.float32(alpha):
+            run += 1
+        lockstep_step(eng, orc, st, TOL["fp32"])
+        assert st.lens[-1] == run + 1
+    assert max(st.lens) >= 4 and st.excused_accepts == 0
+    assert orc.x[:len(prompt) + 60] == future[:len(prompt) + 60]
+    for layer in range(s.n_layers):
+        for pos in (0, len(prompt) - 1, len(prompt) + 7, orc.ctx - 1):
+            k, v = eng.get_kv_row(0, layer, pos)
+            assert np.abs(k - orc.kc[layer][pos].reshape(-1)).max() < 1e-4
+            assert np.abs(v - orc.vc[layer][pos].reshape(-1)).max() < 1e-4
+    state = eng.get_buffer(pkg.BUF_STATE)
+    assert state[0] == len(orc.x) and state[1] == orc.ctx and state[2] == st.lens[-1]
+    eng.close()
