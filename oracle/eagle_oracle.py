@@ -29,6 +29,9 @@ Readings where the paper is silent or garbled (listed in full in the design note
   * the residual line of Alg. 1 is read vector-wise: p <- norm(max(0, p - q_i))
   * accept test r < p/q is evaluated as r*q < p; ties in argmax / top-k go to the lowest token id
   * uniforms come from a counter-based integer generator (24-bit dyadic fractions, exact in fp32)
+  * the paper says nothing about KV storage; a bf16 model keeps its KV cache in bf16, so with
+    kv_store="bf16" every K/V row is rounded to bf16 (nearest-even) when it is written to the cache --
+    a storage code both sides must produce identically -- and read back as that value
 
 PARITY UNPINNED (no value in the paper to compare with): the logits / features of the random-init
 models, and the default tree shapes (the paper's tree figure is not available in text form).
@@ -131,6 +134,13 @@ def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
     return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
 
 
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to bfloat16, returned in x's dtype (the value a bf16 cache entry holds)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16) << np.uint64(16)
+    return u.astype(np.uint32).view(np.float32).astype(x.dtype)
+
+
 def softmax(z: np.ndarray) -> np.ndarray:
     z = z - np.max(z, axis=-1, keepdims=True)
     e = np.exp(z)
@@ -203,12 +213,15 @@ def multi_round(p: np.ndarray, ts: Sequence[int], qs: Sequence[np.ndarray], rs: 
 # ----------------------------------------------------------------------------- the model
 class Oracle:
     def __init__(self, shape, weights: Dict[str, np.ndarray], parent, rank, *, temperature: float = 0.0,
-                 seed: int = 0, seq_id: int = 0, max_seq: int = 4096, dtype=np.float64):
+                 seed: int = 0, seq_id: int = 0, max_seq: int = 4096, dtype=np.float64, kv_store: Optional[str] = None):
         self.s = shape
         self.dt = np.dtype(dtype).type
         self.W = {k: np.asarray(v, dtype=dtype) for k, v in weights.items()}
         self.tree = Tree(parent, rank)
         self.T = float(temperature)
+        if kv_store not in (None, "bf16"):
+            raise ValueError("kv_store must be None (cache holds the computed values) or 'bf16'")
+        self.kv_store = kv_store
         self.seed, self.seq_id, self.step = int(seed), int(seq_id), 0
         s = shape
         self.kc = [np.zeros((max_seq, s.n_kv_heads, s.head_dim), dtype) for _ in range(s.n_layers)]
@@ -256,8 +269,8 @@ class Oracle:
         q = rope((x @ self._lw(prefix, "wq").T).reshape(R, s.n_heads, s.head_dim), pos, s.rope_theta)
         k = rope((x @ self._lw(prefix, "wk").T).reshape(R, s.n_kv_heads, s.head_dim), pos, s.rope_theta)
         v = (x @ self._lw(prefix, "wv").T).reshape(R, s.n_kv_heads, s.head_dim)
-        kc[slots] = k
-        vc[slots] = v
+        kc[slots] = round_bf16(k) if self.kv_store == "bf16" else k
+        vc[slots] = round_bf16(v) if self.kv_store == "bf16" else v
         Tn = visible.shape[1]
         group = s.n_heads // s.n_kv_heads
         scale = self.dt(1.0 / math.sqrt(s.head_dim))

@@ -20,7 +20,7 @@ def make_pair(shape_name, tree, seed, *, max_seq=256, temperature=0.0, rng_seed=
     eng = pkg.Eagle(s, par, rk, max_seq=max_seq, temperature=temperature, seed=rng_seed)
     eng.load_weights(synth.iter_weights(s, seed, synth.device_fmt(s)))
     orc = Oracle(s, synth.make_weights(s, seed, synth.oracle_fmt(s)), par, rk, max_seq=max_seq,
-                 temperature=temperature, seed=rng_seed, dtype=dtype)
+                 temperature=temperature, seed=rng_seed, dtype=dtype, kv_store="bf16" if s.dtype == "bf16" else None)
     return s, eng, orc
 
 
@@ -78,3 +78,36 @@ def test_tiny_hint_knob_accept_lengths_and_compaction():
     state = eng.get_buffer(pkg.BUF_STATE)
     assert state[0] == len(orc.x) and state[1] == orc.ctx and state[2] == st.lens[-1]
     eng.close()
+
+
+def run_twin(shape_name, tree, seed, n_layers, prompt_len, n_new, alpha, max_seq=512):
+    s, eng, orc = make_pair(shape_name, tree, seed=seed, max_seq=max_seq, dtype=np.float32, n_layers=n_layers)
+    prompt = synth.prompt(seed, prompt_len, s.vocab)
+    print(f"{s.name}: prefill", flush=True)
+    # the knob follows the GPU's own vanilla continuation (as the benchmark does)
+    first = eng.prefill(0, prompt)
+    future = list(prompt) + [first]
+    for _ in range(n_new + 8):
+        future.append(int(eng.vanilla_step()[0]))
+    eng.reset()
+    check_prefill(eng, orc, prompt, TOL["bf16"])
+    if alpha > 0:
+        eng.set_hint(0, future, alpha, 30.0, 77)
+        orc.set_hint(future, alpha, 30.0, 77)
+    st = Stats()
+    while len(orc.x) < len(prompt) + n_new:
+        lockstep_step(eng, orc, st, TOL["bf16"])
+    print(f"{s.name}: steps={st.steps} tau={st.tau:.2f} max|dL|={st.max_logit_err:.2e} max|dF|={st.max_feat_err:.2e} "
+          f"draft {st.max_draft_logit_err:.2e}/{st.max_draft_feat_err:.2e} excused tree/accept="
+          f"{st.excused_tree_slots}/{st.excused_accepts} lens={st.lens}", flush=True)
+    toks = list(eng.get_buffer(pkg.BUF_TOKENS))
+    assert toks == orc.x
+    eng.close()
+    return st, toks, future
+
+
+def test_llama7b_twin_bf16_lockstep():
+    """LLaMA2-7B widths (d 4096, 32x128 heads, FFN 11008, vocab 32000), 2 target layers, bf16, T26, knob on."""
+    st, toks, future = run_twin("llama2-7b", "T26", seed=2, n_layers=2, prompt_len=96, n_new=48, alpha=0.7773)
+    assert toks[:96 + 48] == future[:96 + 48]          # speculative == the GPU's vanilla decoding
+    assert st.tau > 2.0

@@ -57,6 +57,16 @@ def test_rope_is_a_rotation_with_relative_phase():
     assert np.count_nonzero(y) == 2
 
 
+def test_round_bf16_is_nearest_even_on_known_values():
+    # 1 + 2^-8 lies exactly between the bf16 neighbours 1 and 1 + 2^-7: ties go to the even mantissa (1.0);
+    # 1 + 3*2^-8 lies between 1 + 2^-7 (odd) and 1 + 2^-6 (even) -> rounds up
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -8, -0.3], dtype=np.float32)
+    y = eo.round_bf16(x)
+    np.testing.assert_array_equal(y[:4], np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6], np.float32))
+    assert abs(y[4] + 0.3) <= 2.0 ** -10 and (y.view(np.uint32) & 0xFFFF == 0).all()
+    assert np.array_equal(eo.round_bf16(synth.normal(1, 2, 64, 0.02, 0.0, "f32")), synth.normal(1, 2, 64, 0.02, 0.0, "bf16_f32"))
+
+
 def test_topk_and_argmax_ties_go_to_lowest_id():
     s = np.array([1.0, 5.0, 5.0, 3.0, 5.0])
     assert eo.topk_desc(s, 4) == [1, 2, 4, 3]
@@ -116,14 +126,15 @@ def test_head_parameter_counts_match_the_paper():
 
 
 # ----------------------------------------------------------------------------- whole greedy loop
-@pytest.mark.parametrize("shape,tree", [("tiny", "T15"), ("tiny", "T26"), ("mini-gqa", "T10"), ("mini-moe", "T15")])
-def test_greedy_speculative_equals_vanilla(shape, tree):
+@pytest.mark.parametrize("shape,tree,kv", [("tiny", "T15", None), ("tiny", "T26", None), ("mini-gqa", "T10", "bf16"),
+                                           ("mini-moe", "T15", "bf16")])
+def test_greedy_speculative_equals_vanilla(shape, tree, kv):
     s = synth.SHAPES[shape]
     W = synth.make_weights(s, 3, synth.oracle_fmt(s))
     par, rk = synth.TREES[tree]
     prompt = synth.prompt(3, 32, s.vocab)
-    a, lens = Oracle(s, W, par, rk, max_seq=192).generate(prompt, 64)
-    b = Oracle(s, W, par, rk, max_seq=192).generate_vanilla(prompt, 64)
+    a, lens = Oracle(s, W, par, rk, max_seq=192, kv_store=kv).generate(prompt, 64)
+    b = Oracle(s, W, par, rk, max_seq=192, kv_store=kv).generate_vanilla(prompt, 64)
     assert a == b
     D = Tree(par, rk).D
     assert all(1 <= n <= D + 1 for n in lens)
