@@ -145,13 +145,11 @@ def main() -> int:
         from oracle.eagle_oracle import Oracle
         cp = args.cpu_prompt
         Wo = synth.make_weights(shape, args.seed, synth.oracle_fmt(shape))
-        orc = Oracle(shape, Wo, par, rk, max_seq=cp + (args.cpu_steps + 1) * (D + 1) + M + 8, dtype=np.float32,
-                     kv_store="bf16" if shape.dtype == "bf16" else None)
+        orc = Oracle(shape, Wo, par, rk, max_seq=cp + (args.cpu_steps + 1) * (D + 1) + M + 8, dtype=np.float32)
         cprompt = prompt[:cp]
         # the knob needs the target's greedy continuation of THIS prompt: the oracle's own vanilla run (untimed)
         n_fut = (args.cpu_steps + 1) * (D + 1)
-        van = Oracle(shape, Wo, par, rk, max_seq=cp + n_fut + 8, dtype=np.float32,
-                     kv_store="bf16" if shape.dtype == "bf16" else None)
+        van = Oracle(shape, Wo, par, rk, max_seq=cp + n_fut + 8, dtype=np.float32)
         cfuture = list(cprompt) + van.generate_vanilla(cprompt, n_fut)
         del van
         orc.set_hint(cfuture, alpha, 30.0, hint_seed)

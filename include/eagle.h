@@ -43,7 +43,8 @@ enum { EAGLE_OK = 0, EAGLE_EINVAL = -1, EAGLE_ENOMEM = -2, EAGLE_ESEQ_FULL = -3,
 enum { EAGLE_F32 = 0, EAGLE_BF16 = 1 };
 
 typedef struct {
-  int32_t dtype;                      /* EAGLE_F32 | EAGLE_BF16: type of the weight matrices and of the KV cache */
+  int32_t dtype;                      /* EAGLE_F32 | EAGLE_BF16: type of the weight matrices (and of the embedding) */
+  int32_t kv_dtype;                   /* EAGLE_F32 | EAGLE_BF16: storage type of the KV cache entries */
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t n_experts, experts_per_tok; /* 0,0 = dense MLP; else top-k routed SwiGLU experts */
   int32_t draft_moe;                  /* the head's decoder layer is a MoE layer too */

@@ -33,7 +33,7 @@ EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weig
 
 
 class EagleConfig(ctypes.Structure):
-    _fields_ = [("dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32),
+    _fields_ = [("dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32),
                 ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("d_ffn", ctypes.c_int32), ("vocab", ctypes.c_int32), ("n_experts", ctypes.c_int32),
                 ("experts_per_tok", ctypes.c_int32), ("draft_moe", ctypes.c_int32), ("rms_eps", ctypes.c_float),
@@ -101,10 +101,12 @@ def _p32(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
 
 
-def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0):
+def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
+                kv_dtype="fp32"):
     parent = np.ascontiguousarray(parent, dtype=np.int32)
     rank = np.ascontiguousarray(rank, dtype=np.int32)
-    cfg = EagleConfig(dtype=EAGLE_F32 if shape.dtype == "fp32" else EAGLE_BF16, n_layers=shape.n_layers,
+    cfg = EagleConfig(dtype=EAGLE_F32 if shape.dtype == "fp32" else EAGLE_BF16,
+                      kv_dtype=EAGLE_F32 if kv_dtype == "fp32" else EAGLE_BF16, n_layers=shape.n_layers,
                       d_model=shape.d_model, n_heads=shape.n_heads, n_kv_heads=shape.n_kv_heads,
                       head_dim=shape.head_dim, d_ffn=shape.d_ffn, vocab=shape.vocab, n_experts=shape.n_experts,
                       experts_per_tok=shape.experts_per_tok, draft_moe=int(shape.draft_moe), rms_eps=shape.rms_eps,
@@ -118,7 +120,7 @@ class Eagle:
     """One libeagle context on cuda:0 (ROCm).  Methods are the C calls, with numpy in/out."""
 
     def __init__(self, shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
-                 device="cuda:0"):
+                 kv_dtype="fp32", device="cuda:0"):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -126,7 +128,7 @@ class Eagle:
             raise RuntimeError("libeagle needs a GPU (no CPU fallback exists)")
         self.shape, self.device = shape, torch.device(device)
         self.cfg = make_config(shape, parent, rank, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
-                               temperature=temperature, seed=seed)
+                               temperature=temperature, seed=seed, kv_dtype=kv_dtype)
         self.M = len(parent)
         depth = [0] * self.M
         for v in range(1, self.M):

@@ -54,8 +54,8 @@ struct eagle_ctx {
   eagle_config cfg;
   hipStream_t stream;
   char* ws; size_t ws_bytes;
-  bool f32;
-  int NWP, NXP, elt;                 // weight planes, activation planes, bytes per model-dtype element
+  bool f32, kv_f32;
+  int NWP, NXP, elt, kv_elt;         // weight planes, activation planes, bytes per weight / per KV element
   TreeDev tree_h; TreeDev* tree_d;
   int M, D, Mmax, max_level_rows;
   // weights
@@ -132,6 +132,7 @@ static int build_tree(const eagle_config* cfg, TreeDev* t) {
 static int check_cfg(const eagle_config* c) {
   if (!c) return fail(EAGLE_EINVAL, "null config");
   if (c->dtype != EAGLE_F32 && c->dtype != EAGLE_BF16) return fail(EAGLE_EINVAL, "dtype must be EAGLE_F32 or EAGLE_BF16");
+  if (c->kv_dtype != EAGLE_F32 && c->kv_dtype != EAGLE_BF16) return fail(EAGLE_EINVAL, "kv_dtype must be EAGLE_F32 or EAGLE_BF16");
   if (c->n_layers < 1 || c->d_model < 16 || c->d_model % 16) return fail(EAGLE_EINVAL, "d_model must be a positive multiple of 16");
   if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 32) return fail(EAGLE_EINVAL, "head_dim must be 32, 64 or 128");
   if (c->n_heads < 1 || c->n_kv_heads < 1 || c->n_heads % c->n_kv_heads) return fail(EAGLE_EINVAL, "n_heads must be a multiple of n_kv_heads");
@@ -192,10 +193,10 @@ static size_t layout(eagle_ctx* c) {
   c->page_shift = 0;
   while ((1 << c->page_shift) < g.page_tokens) c->page_shift++;
   c->layer_stride = (size_t)B * c->pps * KVH * g.page_tokens * dh;
-  c->kc = a.take<char>(c->layer_stride * g.n_layers * c->elt);
-  c->vc = a.take<char>(c->layer_stride * g.n_layers * c->elt);
-  c->dkc = a.take<char>(c->layer_stride * c->elt);
-  c->dvc = a.take<char>(c->layer_stride * c->elt);
+  c->kc = a.take<char>(c->layer_stride * g.n_layers * c->kv_elt);
+  c->vc = a.take<char>(c->layer_stride * g.n_layers * c->kv_elt);
+  c->dkc = a.take<char>(c->layer_stride * c->kv_elt);
+  c->dvc = a.take<char>(c->layer_stride * c->kv_elt);
   c->page_table = a.take<int>((size_t)B * c->pps);
   // state
   c->st.ctx_len = a.take<int>(B); c->st.n_pend = a.take<int>(B); c->st.n_tok = a.take<int>(B);
@@ -254,6 +255,7 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   if (rc) return rc;
   c->f32 = cfg->dtype == EAGLE_F32;
   c->NWP = c->f32 ? 3 : 1; c->NXP = c->f32 ? 3 : 2; c->elt = c->f32 ? 4 : 2;
+  c->kv_f32 = cfg->kv_dtype == EAGLE_F32; c->kv_elt = c->kv_f32 ? 4 : 2;
   c->M = c->tree_h.M; c->D = c->tree_h.D;
   c->max_level_rows = 1;
   for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
@@ -465,7 +467,7 @@ static KVCache kv_for(eagle_ctx* c, int li) {
   bool head = li == g.n_layers;
   char* kb = (char*)(head ? c->dkc : c->kc);
   char* vb = (char*)(head ? c->dvc : c->vc);
-  size_t off = head ? 0 : (size_t)li * c->layer_stride * c->elt;
+  size_t off = head ? 0 : (size_t)li * c->layer_stride * c->kv_elt;
   kv.k = kb + off; kv.v = vb + off;
   kv.page_table = c->page_table; kv.pages_per_seq = c->pps; kv.page_shift = c->page_shift;
   kv.n_kv_heads = g.n_kv_heads; kv.head_dim = g.head_dim;
@@ -490,7 +492,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   if ((rc = gemm(c, w.qkv, c->xf_d, MT, &S))) return rc;
   {
     dim3 grid(M, H + 2 * KVH);
-    if (c->f32) k_qkv_rope_store<float><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
+    if (c->kv_f32) k_qkv_rope_store<float><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
     else k_qkv_rope_store<bf16_t><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
     LAUNCH_CHECK();
   }
@@ -500,7 +502,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     dim3 grid(n_splits, H, pass.n_seq * rblocks);
     float scale = 1.0f / std::sqrt((float)dh);
 #define ATTN(CT, DH) k_attn<CT, DH><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale)
-    if (c->f32) { if (dh == 128) ATTN(float, 128); else if (dh == 64) ATTN(float, 64); else ATTN(float, 32); }
+    if (c->kv_f32) { if (dh == 128) ATTN(float, 128); else if (dh == 64) ATTN(float, 64); else ATTN(float, 32); }
     else { if (dh == 128) ATTN(bf16_t, 128); else if (dh == 64) ATTN(bf16_t, 64); else ATTN(bf16_t, 32); }
 #undef ATTN
     LAUNCH_CHECK();
@@ -695,7 +697,7 @@ static int do_accept(eagle_ctx* c) {
   LAUNCH_CHECK();
   dim3 grid(4, g.n_layers + 1, B);
   KVCache kv = kv_for(c, 0);
-  if (c->f32) k_compact<float><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
+  if (c->kv_f32) k_compact<float><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
   else k_compact<bf16_t><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
   LAUNCH_CHECK();
   c->phase = 0;
@@ -767,7 +769,7 @@ extern "C" int eagle_step(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, i
     }
     double kvb = 0;
     for (int s = 0; s < c->n_active; ++s)   // context read once + the tree's own rows written
-      kvb += 2.0 * g.n_layers * g.n_kv_heads * g.head_dim * c->elt * (double)(ctx_before[s] + c->M);
+      kvb += 2.0 * g.n_layers * g.n_kv_heads * g.head_dim * c->kv_elt * (double)(ctx_before[s] + c->M);
     wbytes += (double)c->n_active * c->M * g.vocab * 4.0;   // logits written
     c->prof.verify_weight_bytes += wbytes; c->prof.verify_kv_bytes += kvb;
     if (c->prof_mode == 2 && (rc = collect_gemm_events(c))) return rc;
@@ -865,7 +867,7 @@ extern "C" int eagle_get_kv_row(eagle_ctx* c, int32_t seq, int32_t layer, int32_
   float* tmp = c->featbuf;   // scratch, idle between passes
   if ((size_t)2 * n > (size_t)c->Mmax * g.d_model) return fail(EAGLE_EINVAL, "internal: scratch too small");
   KVCache kv = kv_for(c, li);
-  if (c->f32) k_read_kv_row<float><<<4, 256, 0, c->stream>>>(kv, seq, pos, tmp, tmp + n);
+  if (c->kv_f32) k_read_kv_row<float><<<4, 256, 0, c->stream>>>(kv, seq, pos, tmp, tmp + n);
   else k_read_kv_row<bf16_t><<<4, 256, 0, c->stream>>>(kv, seq, pos, tmp, tmp + n);
   LAUNCH_CHECK();
   HIPCHK(hipMemcpyAsync(k_host, tmp, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream));

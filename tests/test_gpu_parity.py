@@ -12,15 +12,16 @@ pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 
-def make_pair(shape_name, tree, seed, *, max_seq=256, temperature=0.0, rng_seed=0, dtype=np.float64, n_layers=None):
+def make_pair(shape_name, tree, seed, *, max_seq=256, temperature=0.0, rng_seed=0, dtype=np.float64, n_layers=None,
+              kv_dtype="fp32"):
     s = synth.SHAPES[shape_name]
     if n_layers is not None:
         s = s.twin(n_layers)
     par, rk = synth.TREES[tree]
-    eng = pkg.Eagle(s, par, rk, max_seq=max_seq, temperature=temperature, seed=rng_seed)
+    eng = pkg.Eagle(s, par, rk, max_seq=max_seq, temperature=temperature, seed=rng_seed, kv_dtype=kv_dtype)
     eng.load_weights(synth.iter_weights(s, seed, synth.device_fmt(s)))
     orc = Oracle(s, synth.make_weights(s, seed, synth.oracle_fmt(s)), par, rk, max_seq=max_seq,
-                 temperature=temperature, seed=rng_seed, dtype=dtype, kv_store="bf16" if s.dtype == "bf16" else None)
+                 temperature=temperature, seed=rng_seed, dtype=dtype, kv_store="bf16" if kv_dtype == "bf16" else None)
     return s, eng, orc
 
 
