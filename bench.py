@@ -24,6 +24,9 @@ sys.path.insert(0, ROOT)
 import numpy as np  # noqa: E402
 
 
+HINT_BIAS = 1.0e4   # far above any head logit (a random-init head feeds its own growing features back)
+
+
 def solve_alpha(tau: float, D: int) -> float:
     lo, hi = 0.0, 0.999999
     for _ in range(60):
@@ -90,7 +93,7 @@ def main() -> int:
     def run(mode: int, steps: int):
         eng.reset()
         eng.prefill(0, prompt)
-        eng.set_hint(0, future, alpha, 30.0, hint_seed)
+        eng.set_hint(0, future, alpha, HINT_BIAS, hint_seed)
         eng.set_profiling(0)
         for _ in range(W):
             eng.step()
@@ -152,7 +155,7 @@ def main() -> int:
         van = Oracle(shape, Wo, par, rk, max_seq=cp + n_fut + 8, dtype=np.float32)
         cfuture = list(cprompt) + van.generate_vanilla(cprompt, n_fut)
         del van
-        orc.set_hint(cfuture, alpha, 30.0, hint_seed)
+        orc.set_hint(cfuture, alpha, HINT_BIAS, hint_seed)
         orc.prefill(cprompt)
         tc = time.perf_counter()
         em = 0

@@ -161,7 +161,6 @@ static size_t layout(eagle_ctx* c) {
   Arena a(c->ws);
   const int d = g.d_model, V = g.vocab, H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn, B = g.max_batch;
   const int M = c->M, D1 = c->D + 1;
-  const int Fpad = (F + 31) / 32 * 32;     // the up rows start on a 32-row tile boundary
   c->tree_d = a.take<TreeDev>(1);
   c->rope_cos = a.take<float>((size_t)g.max_seq * dh / 2);
   c->rope_sin = a.take<float>((size_t)g.max_seq * dh / 2);
@@ -179,10 +178,10 @@ static size_t layout(eagle_ctx* c) {
     w.moe = g.n_experts > 0 && (l < g.n_layers || g.draft_moe);
     if (w.moe) {
       w.e_gu.resize(g.n_experts); w.e_dn.resize(g.n_experts);
-      for (int e = 0; e < g.n_experts; ++e) { take_packed(a, w.e_gu[e], Fpad + F, d, c->NWP); take_packed(a, w.e_dn[e], d, F, c->NWP); }
+      for (int e = 0; e < g.n_experts; ++e) { take_packed(a, w.e_gu[e], 2 * F, d, c->NWP); take_packed(a, w.e_dn[e], d, F, c->NWP); }
       w.router = a.take<float>((size_t)g.n_experts * d);
     } else {
-      take_packed(a, w.gu, Fpad + F, d, c->NWP);
+      take_packed(a, w.gu, 2 * F, d, c->NWP);
       take_packed(a, w.dn, d, F, c->NWP);
     }
     w.attn_norm = a.take<float>(d);
@@ -339,12 +338,17 @@ extern "C" void eagle_free(eagle_ctx* c) {
 }
 
 // ---------------------------------------------------------------------------- weights
-static int pack_into(eagle_ctx* c, const void* src, PackedW& w, int N, int K, int row_offset) {
-  if (K != w.K || row_offset % 32 || row_offset + N > w.Npad) return fail(EAGLE_EINVAL, "internal: pack shape mismatch");
+static int pack_into(eagle_ctx* c, const void* src, PackedW& w, int N, int K, int row_offset, int mode = PACK_PLAIN) {
+  if (K != w.K || row_offset % 32) return fail(EAGLE_EINVAL, "internal: pack shape mismatch");
+  int last = mode == PACK_PLAIN ? row_offset + (N + 31) / 32 * 32 : row_offset + pack_row_map(mode, N - 1, c->cfg.head_dim) + 1;
+  if (mode == PACK_ROPE) last = row_offset + N;
+  if (last > w.Npad) return fail(EAGLE_EINVAL, "internal: packed rows overflow");
+  if (mode == PACK_ROPE && N % c->cfg.head_dim) return fail(EAGLE_EINVAL, "internal: rope packing needs whole heads");
+  if ((mode == PACK_GATE || mode == PACK_UP) && N % 16) return fail(EAGLE_EINVAL, "d_ffn must be a multiple of 16");
   size_t total = (size_t)((N + 31) / 32) * w.KS * 64;
   int blocks = (int)((total + 255) / 256);
-  if (c->f32) k_pack_weight<float><<<blocks, 256, 0, c->stream>>>((const float*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride);
-  else k_pack_weight<bf16_t><<<blocks, 256, 0, c->stream>>>((const bf16_t*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride);
+  if (c->f32) k_pack_weight<float><<<blocks, 256, 0, c->stream>>>((const float*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride, mode, c->cfg.head_dim);
+  else k_pack_weight<bf16_t><<<blocks, 256, 0, c->stream>>>((const bf16_t*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride, mode, c->cfg.head_dim);
   LAUNCH_CHECK();
   return EAGLE_OK;
 }
@@ -357,7 +361,7 @@ extern "C" int eagle_load_weight(eagle_ctx* c, int32_t which, int32_t layer, con
   if (!c || !src) return fail(EAGLE_EINVAL, "null argument");
   if (which < 0 || which >= EAGLE_W_COUNT) return fail(EAGLE_EINVAL, "unknown tensor id %d", which);
   const eagle_config& g = c->cfg;
-  const int d = g.d_model, H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn, Fpad = (F + 31) / 32 * 32;
+  const int d = g.d_model, H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn;
   int rc = EAGLE_OK;
   if (which < EAGLE_W_ATTN_NORM) {
     switch (which) {
@@ -378,8 +382,8 @@ extern "C" int eagle_load_weight(eagle_ctx* c, int32_t which, int32_t layer, con
   switch (which) {
     case EAGLE_W_ATTN_NORM: HIPCHK(hipMemcpyAsync(w.attn_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
     case EAGLE_W_MLP_NORM: HIPCHK(hipMemcpyAsync(w.mlp_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
-    case EAGLE_W_Q: rc = pack_into(c, src, w.qkv, H * dh, d, 0); break;
-    case EAGLE_W_K: rc = pack_into(c, src, w.qkv, KVH * dh, d, H * dh); break;
+    case EAGLE_W_Q: rc = pack_into(c, src, w.qkv, H * dh, d, 0, PACK_ROPE); break;
+    case EAGLE_W_K: rc = pack_into(c, src, w.qkv, KVH * dh, d, H * dh, PACK_ROPE); break;
     case EAGLE_W_V: rc = pack_into(c, src, w.qkv, KVH * dh, d, (H + KVH) * dh); break;
     case EAGLE_W_O: rc = pack_into(c, src, w.o, d, H * dh, 0); break;
     case EAGLE_W_ROUTER:
@@ -389,8 +393,8 @@ extern "C" int eagle_load_weight(eagle_ctx* c, int32_t which, int32_t layer, con
       break;
     case EAGLE_W_GATE:
     case EAGLE_W_UP:
-      if (w.moe) for (int e = 0; e < g.n_experts && !rc; ++e) rc = pack_into(c, s + (size_t)e * F * d * c->elt, w.e_gu[e], F, d, which == EAGLE_W_UP ? Fpad : 0);
-      else rc = pack_into(c, src, w.gu, F, d, which == EAGLE_W_UP ? Fpad : 0);
+      if (w.moe) for (int e = 0; e < g.n_experts && !rc; ++e) rc = pack_into(c, s + (size_t)e * F * d * c->elt, w.e_gu[e], F, d, 0, which == EAGLE_W_UP ? PACK_UP : PACK_GATE);
+      else rc = pack_into(c, src, w.gu, F, d, 0, which == EAGLE_W_UP ? PACK_UP : PACK_GATE);
       break;
     case EAGLE_W_DOWN:
       if (w.moe) for (int e = 0; e < g.n_experts && !rc; ++e) rc = pack_into(c, s + (size_t)e * d * F * c->elt, w.e_dn[e], d, F, 0);
@@ -515,7 +519,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   if ((rc = gemm(c, w.gu, c->xf_d, MT, &S))) return rc;
   {
     dim3 grid((F / 8 + 255) / 256, M);
-    k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, (F + 31) / 32 * 32, c->xf_ffn, MT, c->NXP);
+    k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
     LAUNCH_CHECK();
   }
   if ((rc = gemm(c, w.dn, c->xf_ffn, MT, &S))) return rc;

@@ -129,12 +129,27 @@ __device__ inline void block_argmax(float& v, int& i, float* shv, int* shi) {
 }
 
 // ============================================================================ weight packing
-// src: row-major [N][K] (float or bf16).  dst: nplanes packed planes (see wpack_index), rows
-// [row_offset, row_offset+N) of a matrix with KS k-steps; plane p starts at dst + p*plane_stride.
+// src: row-major [N][K] (float or bf16).  dst: nplanes packed planes (see wpack_index) of a matrix with KS k-steps;
+// plane p starts at dst + p*plane_stride.  Source row n lands in packed row row_offset + map(n):
+//   PACK_PLAIN  map(n) = n
+//   PACK_ROPE   rows of a head are interleaved so that the two members of a rotate-half pair (i, i + dh/2) become
+//               neighbours: head*dh + i + half*dh/2  ->  head*dh + 2i + half
+//   PACK_GATE / PACK_UP  fused gate/up matrix: every 32-row block holds gate rows 16j..16j+15 then up rows
+//               16j..16j+15, so SwiGLU partners sit in the same block
 // One thread builds one 16-byte lane chunk (8 elements along k) of every plane.
+enum { PACK_PLAIN = 0, PACK_ROPE = 1, PACK_GATE = 2, PACK_UP = 3 };
+__host__ __device__ inline int pack_row_map(int mode, int n, int dh) {
+  if (mode == PACK_ROPE) {
+    int head = n / dh, r = n % dh, half = dh >> 1;
+    return head * dh + 2 * (r % half) + r / half;
+  }
+  if (mode == PACK_GATE) return (n >> 4) * 32 + (n & 15);
+  if (mode == PACK_UP) return (n >> 4) * 32 + 16 + (n & 15);
+  return n;
+}
 template <typename SrcT>
 __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ src, bf16_t* __restrict__ dst, int N, int K,
-                                                     int row_offset, int KS, int nplanes, size_t plane_stride) {
+                                                     int row_offset, int KS, int nplanes, size_t plane_stride, int mode, int dh) {
   size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   int nrb = (N + 31) >> 5;
   size_t total = (size_t)nrb * KS * 64;
@@ -145,6 +160,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
   int rb = tile / KS;
   int n = rb * 32 + (lane & 31);
   int k0 = ks * 16 + (lane >> 5) * 8;
+  if (n >= N && mode != PACK_PLAIN) return;               // only the plain map pads its last block with zero rows
   bf16_t out[3][8];
   for (int t = 0; t < 8; ++t) {
     float x = 0.f;
@@ -156,7 +172,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
     split_bf16(x, p, nplanes);
     for (int q = 0; q < nplanes; ++q) out[q][t] = p[q];
   }
-  size_t o = wpack_index(row_offset + n, k0, KS);       // row_offset is a multiple of 32
+  size_t o = wpack_index(row_offset + pack_row_map(mode, n, dh), k0, KS);
   for (int q = 0; q < nplanes; ++q) {
     u32x4 v;
     v.x = out[q][0] | ((uint32_t)out[q][1] << 16); v.y = out[q][2] | ((uint32_t)out[q][3] << 16);
@@ -368,7 +384,9 @@ __global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev*
   RowInfo ri = row_info(pass, tree, st, r);
   const int dh = kv.head_dim, half = dh >> 1, KVH = kv.n_kv_heads;
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
-    int n1 = hd * dh + i, n2 = n1 + half;
+    // q/k heads are packed with rotate-half partners adjacent (PACK_ROPE); v heads keep their order
+    int n1 = hd < H + KVH ? hd * dh + 2 * i : hd * dh + i;
+    int n2 = hd < H + KVH ? n1 + 1 : n1 + half;
     float a = 0.f, b = 0.f;
     for (int s = 0; s < S; ++s) {
       a += PT[((size_t)s * Npad + n1) * Mpad + r];
@@ -531,8 +549,8 @@ __global__ __launch_bounds__(256) void k_attn_combine(const float* __restrict__ 
 }
 
 // ============================================================================ SwiGLU and logits epilogues
-// act[r][k] = silu(gate) * up, gate = sum_s PT[s][k][r], up = sum_s PT[s][up_off + k][r]   (F = d_ffn)
-__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, int S, int Npad, int Mpad, int F, int up_off,
+// act[r][k] = silu(gate) * up with the fused matrix's row order (PACK_GATE / PACK_UP)   (F = d_ffn)
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, int S, int Npad, int Mpad, int F,
                                                 bf16_t* XF, int MT, int nplanes) {
   int r = blockIdx.y;
   int k8 = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
@@ -541,8 +559,8 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, in
   for (int t = 0; t < 8; ++t) {
     float g = 0.f, u = 0.f;
     for (int s = 0; s < S; ++s) {
-      g += PT[((size_t)s * Npad + k8 + t) * Mpad + r];
-      u += PT[((size_t)s * Npad + up_off + k8 + t) * Mpad + r];
+      g += PT[((size_t)s * Npad + pack_row_map(PACK_GATE, k8 + t, 0)) * Mpad + r];
+      u += PT[((size_t)s * Npad + pack_row_map(PACK_UP, k8 + t, 0)) * Mpad + r];
     }
     x[t] = g / (1.0f + __expf(-g)) * u;
   }

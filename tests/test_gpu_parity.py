@@ -93,8 +93,8 @@ def run_twin(shape_name, tree, seed, n_layers, prompt_len, n_new, alpha, max_seq
     eng.reset()
     check_prefill(eng, orc, prompt, TOL["bf16"])
     if alpha > 0:
-        eng.set_hint(0, future, alpha, 30.0, 77)
-        orc.set_hint(future, alpha, 30.0, 77)
+        eng.set_hint(0, future, alpha, 1.0e4, 77)
+        orc.set_hint(future, alpha, 1.0e4, 77)
     st = Stats()
     while len(orc.x) < len(prompt) + n_new:
         lockstep_step(eng, orc, st, TOL["bf16"])
