@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeagle.so")
 SOURCES = ["eagle.hip"]
-HEADERS = ["kernels.h", "common.h", os.path.join("..", "..", "include", "eagle.h")]
+HEADERS = ["kernels.h", "kernels2.h", "common.h", os.path.join("..", "..", "include", "eagle.h")]
 
 
 def needs_build() -> bool:

@@ -2,6 +2,7 @@
 // speculative step (drafting: Sec. 3.1 / App. A.1; verification: Sec. 3.3; acceptance: Sec. 2 / App. A.2).
 #include "../../include/eagle.h"
 #include "kernels.h"
+#include "kernels2.h"
 
 #include <cmath>
 #include <cstdarg>
@@ -76,6 +77,11 @@ struct eagle_ctx {
   float *h, *Q, *PT, *part_o, *part_ml;
   bf16_t *xf_d, *xf_2d, *xf_att, *xf_ffn;
   size_t pt_floats;
+  // fast path (passes of <= 32 rows)
+  float *h2, *PT2, *ssq1, *ssq2; int *cnt_gemm, *cnt_attn; size_t pt2_floats;
+  bf16_t *xf2_d, *xf2_2d, *xf2_att, *xf2_ffn;
+  int ssq1_groups = 0, ssq2_groups = 0;
+  int n_cu = 256;
   // host mirror
   std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
   int n_active = 0;
@@ -95,6 +101,39 @@ static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
   p.ks_per_split = (KS + S - 1) / S;
   p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
   p.chunk = std::max(1, 64 / (NXP * MT));
+  return p;
+}
+
+// Work split of the fast-path GEMM: S K-slices x `groups` row groups = one work-group each; inside a work-group
+// `lanes` x `kparts` waves (product 8): a wave owns every lanes-th row block of the group over one k-part.
+struct Plan2 { int S, groups, lanes, kparts, RW, kt_max; size_t lds; };
+static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
+  Plan2 p;
+  const int x_cap_kb = 128;                                   // LDS given to the X slice / the wave reduction
+  int S = 1;
+  while ((NXP * ((KS + S - 1) / S)) > x_cap_kb) S *= 2;
+  int groups = std::max(1, std::min(NRB, n_cu / S));
+  // few row blocks: split K further (slices of at least 4 k-steps) until the grid fills the chip
+  while (groups * S * 2 <= n_cu && (KS + 2 * S - 1) / (2 * S) >= 4) S *= 2;
+  const int R = (NRB + groups - 1) / groups, kt = (KS + S - 1) / S;
+  const int depth_limit = NWP == 1 ? 6 : 3;                    // row blocks a wave may own (accumulator registers)
+  long best = -1; int bl = 8, bk = 1;
+  const int cand[4][2] = {{8, 1}, {4, 2}, {2, 4}, {1, 8}};
+  for (auto& cd : cand) {
+    int rw = (R + cd[0] - 1) / cd[0];
+    if (rw > depth_limit) continue;
+    int rwt = rw <= 1 ? 1 : rw <= 2 ? 2 : rw <= 3 ? 3 : 6;
+    if ((size_t)cd[0] * (cd[1] - 1) * rwt * 4 > (size_t)x_cap_kb) continue;
+    long cost = (long)rw * ((kt + cd[1] - 1) / cd[1]);
+    if (best < 0 || cost < best) { best = cost; bl = cd[0]; bk = cd[1]; }
+  }
+  if (best < 0) { bl = 8; bk = 1; }                            // caller checks RW against the limit
+  p.S = S; p.groups = groups; p.lanes = bl; p.kparts = bk;
+  int rw = (R + bl - 1) / bl;
+  p.RW = rw <= 1 ? 1 : rw <= 2 ? 2 : rw <= 3 ? 3 : 6;
+  p.kt_max = kt;
+  size_t xs = (size_t)NXP * kt * 1024, red = (size_t)bl * (bk - 1) * p.RW * 4096;
+  p.lds = std::max(xs, red);
   return p;
 }
 
@@ -243,6 +282,26 @@ static size_t layout(eagle_ctx* c) {
   c->PT = a.take<float>(worst);
   c->part_o = a.take<float>((size_t)Mm * H * 16 * dh);
   c->part_ml = a.take<float>((size_t)Mm * H * 16 * 2);
+  // fast path buffers
+  c->h2 = a.take<float>((size_t)32 * d);
+  c->xf2_d = a.take<bf16_t>((size_t)c->NXP * 32 * d);
+  c->xf2_2d = a.take<bf16_t>((size_t)c->NXP * 32 * 2 * d);
+  c->xf2_att = a.take<bf16_t>((size_t)c->NXP * 32 * H * dh);
+  c->xf2_ffn = a.take<bf16_t>((size_t)c->NXP * 32 * F);
+  c->ssq1 = a.take<float>(256 * 32); c->ssq2 = a.take<float>(256 * 32);
+  c->cnt_gemm = a.take<int>(1024); c->cnt_attn = a.take<int>((size_t)64 * H);
+  size_t worst2 = 0;
+  auto consider2 = [&](const PackedW& w) {
+    Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
+    worst2 = std::max(worst2, (size_t)p.S * w.Npad * 32);
+  };
+  consider2(c->lm_head); consider2(c->fc);
+  for (auto& w : c->layers) {
+    consider2(w.qkv); consider2(w.o);
+    if (w.moe) { consider2(w.e_gu[0]); consider2(w.e_dn[0]); } else { consider2(w.gu); consider2(w.dn); }
+  }
+  c->pt2_floats = worst2;
+  c->PT2 = a.take<float>(worst2);
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -572,6 +631,147 @@ static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bo
   return lm_head(c, pass, M, MT, c->draft_logits, 0, 0);
 }
 
+// ---------------------------------------------------------------------------- fast path (<= 32 rows)
+template <int NWP, int NXP, int RW, int DEPTH>
+static hipError_t launch_k2(const Gemm2& g, size_t lds, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm<NWP, NXP, RW, DEPTH>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  k2_gemm<NWP, NXP, RW, DEPTH><<<g.groups * g.S, V2_THREADS, lds, s>>>(g);
+  return hipGetLastError();
+}
+
+// Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
+static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int* groups_out) {
+  Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
+  const int R = (w.NRB + p.groups - 1) / p.groups;
+  if ((R + p.lanes - 1) / p.lanes > p.RW) return fail(EAGLE_EINVAL, "internal: %d row blocks per wave exceed the kernel's %d", (R + p.lanes - 1) / p.lanes, p.RW);
+  if ((size_t)p.S * w.Npad * 32 > c->pt2_floats) return fail(EAGLE_EINVAL, "internal: fast-path partial buffer too small");
+  if (p.groups > 256 || p.lds > 144 * 1024 || p.lanes * p.kparts != 8) return fail(EAGLE_EINVAL, "internal: bad work split");
+  g.W = w.w; g.wps = w.plane_stride; g.NRB = w.NRB; g.KS = w.KS; g.Npad = w.Npad; g.N = w.N;
+  g.XF = XF; g.S = p.S; g.groups = p.groups; g.lanes = p.lanes; g.kparts = p.kparts;
+  g.PT = c->PT2; g.counters = c->cnt_gemm;
+  if (groups_out) *groups_out = p.groups;
+  bool timed = c->prof_mode == 2;
+  if (timed) {
+    if (c->gemm_ev_used + 2 > c->gemm_ev.size())
+      for (int i = 0; i < 512; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
+    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used], c->stream));
+  }
+  hipError_t e;
+  if (c->f32) {
+    switch (p.RW) {
+      case 1: e = launch_k2<3, 3, 1, 4>(g, p.lds, c->stream); break;
+      case 2: e = launch_k2<3, 3, 2, 2>(g, p.lds, c->stream); break;
+      default: e = launch_k2<3, 3, 3, 2>(g, p.lds, c->stream); break;
+    }
+  } else {
+    switch (p.RW) {
+      case 1: e = launch_k2<1, 2, 1, 16>(g, p.lds, c->stream); break;
+      case 2: e = launch_k2<1, 2, 2, 8>(g, p.lds, c->stream); break;
+      case 3: e = launch_k2<1, 2, 3, 5>(g, p.lds, c->stream); break;
+      default: e = launch_k2<1, 2, 6, 3>(g, p.lds, c->stream); break;
+    }
+  }
+  if (e != hipSuccess) return fail(EAGLE_EHIP, "fused gemm launch failed: %s", hipGetErrorString(e));
+  if (timed) {
+    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used + 1], c->stream));
+    c->gemm_ev_used += 2;
+    c->gemm_ev_bytes.push_back((double)w.N * w.K * c->elt);
+  }
+  return EAGLE_OK;
+}
+
+static Gemm2 gemm2_base(eagle_ctx* c, const Pass& pass, int M) {
+  Gemm2 g;
+  memset(&g, 0, sizeof(g));
+  g.M = M; g.pass = pass; g.tree = c->tree_d; g.st = c->st; g.d = c->cfg.d_model;
+  g.rope_cos = c->rope_cos; g.rope_sin = c->rope_sin; g.H = c->cfg.n_heads; g.kv_f32 = c->kv_f32; g.Q = c->Q;
+  return g;
+}
+static RowScale scale_of(eagle_ctx* c, const float* ssq, int groups) {
+  RowScale rs; rs.ssq = ssq; rs.groups = groups; rs.inv_d = 1.0f / (float)c->cfg.d_model; rs.eps = c->cfg.rms_eps;
+  return rs;
+}
+
+// One decoder layer on <= 32 rows.  In: h2 (residual), xf2_d = h2 * (this layer's attn gain), ssq2 (row sums of squares).
+// Out: the same three for the consumer named by next_gain (nullptr: xf2_d = h2 itself).
+static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, int n_new, const float* next_gain) {
+  const eagle_config& cf = c->cfg;
+  LayerW& w = c->layers[li];
+  if (w.moe) return fail(EAGLE_EINVAL, "MoE layers are not implemented yet");
+  const int H = cf.n_heads, dh = cf.head_dim, d = cf.d_model, F = cf.d_ffn;
+  int rc;
+  Gemm2 g = gemm2_base(c, pass, M);
+  g.epi = EPI_QKV; g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups); g.kv = kv_for(c, li);
+  if ((rc = gemm2(c, w.qkv, c->xf2_d, g, nullptr))) return rc;
+  {
+    int n_splits = std::max(1, std::min(16, (ctx_max + 64 + 63) / 64));
+    dim3 grid(n_splits, H, pass.n_seq);
+    float scale = 1.0f / std::sqrt((float)dh);
+    KVCache kv = kv_for(c, li);
+#define ATTN2(CT, DH) k2_attn<CT, DH><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP)
+    if (c->kv_f32) { if (dh == 128) ATTN2(float, 128); else if (dh == 64) ATTN2(float, 64); else ATTN2(float, 32); }
+    else { if (dh == 128) ATTN2(bf16_t, 128); else if (dh == 64) ATTN2(bf16_t, 64); else ATTN2(bf16_t, 32); }
+#undef ATTN2
+    LAUNCH_CHECK();
+  }
+  g = gemm2_base(c, pass, M);
+  g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = w.mlp_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq1;
+  if ((rc = gemm2(c, w.o, c->xf2_att, g, &c->ssq1_groups))) return rc;
+  g = gemm2_base(c, pass, M);
+  g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
+  if ((rc = gemm2(c, w.gu, c->xf2_d, g, nullptr))) return rc;
+  g = gemm2_base(c, pass, M);
+  g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = next_gain; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
+  return gemm2(c, w.dn, c->xf2_ffn, g, &c->ssq2_groups);
+}
+
+static int lm_head2(eagle_ctx* c, const Pass& pass, int M, bool scaled, float* out, int out_kind, int only_last_row) {
+  Gemm2 g = gemm2_base(c, pass, M);
+  g.epi = EPI_LOGITS; g.logits = out; g.out_kind = out_kind; g.V = c->cfg.vocab; g.only_last_row = only_last_row;
+  if (scaled) g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups);
+  return gemm2(c, c->lm_head, c->xf2_d, g, nullptr);
+}
+
+static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, float* logits_out, int out_kind) {
+  const eagle_config& cf = c->cfg;
+  const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
+  int rc;
+  const int eg = std::max(1, std::min(64, d / 64));
+  if (c->f32) k2_embed<float, 3><<<eg, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, (const float*)c->embed, cf.vocab, M, d, c->h2, c->layers[0].attn_norm, c->xf2_d, c->ssq2);
+  else k2_embed<bf16_t, 2><<<eg, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, (const bf16_t*)c->embed, cf.vocab, M, d, c->h2, c->layers[0].attn_norm, c->xf2_d, c->ssq2);
+  LAUNCH_CHECK();
+  c->ssq2_groups = eg;
+  for (int l = 0; l < cf.n_layers; ++l)
+    if ((rc = layer2(c, pass, M, l, ctx_max, n_new, l + 1 < cf.n_layers ? c->layers[l + 1].attn_norm : c->final_norm))) return rc;
+  k2_features<<<M, 256, 0, c->stream>>>(c->h2, scale_of(c, c->ssq2, c->ssq2_groups), c->final_norm, M, d, c->featbuf);
+  LAUNCH_CHECK();
+  k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->featbuf, c->F, c->pend_f, c->chunk_f, d);
+  LAUNCH_CHECK();
+  return lm_head2(c, pass, M, true, logits_out, out_kind, 0);
+}
+
+static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new) {
+  const eagle_config& cf = c->cfg;
+  const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
+  int rc;
+  if (c->f32) k_fc_input<float><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
+  else k_fc_input<bf16_t><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
+  LAUNCH_CHECK();
+  Gemm2 g = gemm2_base(c, pass, M);
+  g.epi = EPI_RESID; g.h_in = nullptr; g.h_out = c->h2; g.bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;
+  g.gain_next = c->layers[cf.n_layers].attn_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
+  if ((rc = gemm2(c, c->fc, c->xf2_2d, g, &c->ssq2_groups))) return rc;
+  if ((rc = layer2(c, pass, M, cf.n_layers, ctx_max, n_new, nullptr))) return rc;
+  k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->h2, c->node_f, c->pend_f, c->chunk_f, d);
+  LAUNCH_CHECK();
+  return lm_head2(c, pass, M, false, c->draft_logits, 0, 0);
+}
+
 // ---------------------------------------------------------------------------- sequence life cycle
 extern "C" int eagle_reset(eagle_ctx* c) {
   if (!c) return fail(EAGLE_EINVAL, "null context");
@@ -667,7 +867,7 @@ static int do_draft(eagle_ctx* c) {
   const int B = c->n_active, D1 = c->D + 1, ctx = max_ctx(c);
   const eagle_config& g = c->cfg;
   Pass p1{PASS_DRAFT_PENDING, D1, B, 0, 0, 0, 0};
-  if ((rc = head_forward(c, p1, ctx + D1, D1, true))) return rc;
+  if ((rc = (D1 * B <= 32 ? head_forward2(c, p1, ctx, D1) : head_forward(c, p1, ctx + D1, D1, true)))) return rc;
   dim3 g0(1, B);
   k_expand<<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
   LAUNCH_CHECK();
@@ -675,7 +875,7 @@ static int do_draft(eagle_ctx* c) {
     int nr = c->tree_h.n_level_rows[lev];
     if (nr == 0) break;
     Pass pl{PASS_DRAFT_LEVEL, nr, B, 0, lev, 0, 0};
-    if ((rc = head_forward(c, pl, ctx + c->M, c->M, true))) return rc;
+    if ((rc = (nr * B <= 32 ? head_forward2(c, pl, ctx, c->M) : head_forward(c, pl, ctx + c->M, c->M, true)))) return rc;
     dim3 gl(nr, B);
     k_expand<<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
     LAUNCH_CHECK();
@@ -687,7 +887,8 @@ static int do_draft(eagle_ctx* c) {
 static int do_verify(eagle_ctx* c) {
   if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
   Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
-  int rc = target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
+  int rc = c->M * c->n_active <= 32 ? target_forward2(c, pv, max_ctx(c), c->M, c->L, 0)
+                                    : target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
   if (rc) return rc;
   c->phase = 2;
   return EAGLE_OK;
@@ -788,7 +989,8 @@ extern "C" int eagle_vanilla_step(eagle_ctx* c, int32_t* tokens) {
   const eagle_config& g = c->cfg;
   const int B = c->n_active;
   Pass pv{PASS_VANILLA, 1, B, 0, 0, 0, 0};
-  if ((rc = target_forward(c, pv, max_ctx(c) + 1, 1, true, c->vanilla_logits, 1, 0))) return rc;
+  if ((rc = (B <= 32 ? target_forward2(c, pv, max_ctx(c), 1, c->vanilla_logits, 1)
+                     : target_forward(c, pv, max_ctx(c) + 1, 1, true, c->vanilla_logits, 1, 0)))) return rc;
   k_choose<<<B, 1024, 0, c->stream>>>(c->st, 0, c->vanilla_logits, g.vocab, g.temperature, g.seed, c->pbuf, 0, 0, c->D);
   LAUNCH_CHECK();
   std::vector<int> tk(B);

@@ -1,0 +1,493 @@
+// Fast path for passes of at most 32 rows (tree verification at batch 1, the head's tree levels, vanilla
+// decoding): weight-streaming GEMM with the reduction and the layer's element-wise work fused into it.
+//
+//   * A work-group owns (a group of 32-row weight blocks) x (one K slice).  Its K slice of the activations sits
+//     in LDS in MFMA B-operand order; every wave streams its own weight tiles straight from HBM into the MFMA
+//     A operand (one coalesced 1 KiB load per tile, many tiles in flight).
+//   * Waves that share a weight block but split K are summed through LDS in a fixed order; work-groups that
+//     split K write partials and the LAST one to arrive (an atomic counter, no waiting) sums them in split
+//     order and runs the epilogue -- so results do not depend on timing.
+//   * RMSNorm is folded around the GEMM: the producer writes h*gain (not normalised) plus per-row partial sums
+//     of squares; the consumer multiplies its outputs by 1/rms, which commutes with the matrix product.
+#pragma once
+#include "kernels.h"
+
+#define V2_THREADS 512
+
+struct RowScale {            // 1/rms of the rows that produced the GEMM input; ssq == nullptr -> 1
+  const float* ssq;          // [groups][32] partial sums of squares
+  int groups;
+  float inv_d, eps;
+};
+__device__ inline float row_rstd(const RowScale& rs, int m) {
+  if (!rs.ssq) return 1.0f;
+  float a = 0.f;
+  for (int g = 0; g < rs.groups; ++g) a += rs.ssq[g * 32 + m];
+  return 1.0f / sqrtf(a * rs.inv_d + rs.eps);
+}
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+
+struct Gemm2 {
+  const bf16_t* W; size_t wps; int NRB, KS, Npad, N;
+  const bf16_t* XF;                       // NXP planes of KS tiles (one 32-row tile per k-step)
+  int S, groups, lanes, kparts;
+  float* PT; int* counters;
+  int M, epi;
+  RowScale in_scale;
+  // EPI_QKV
+  Pass pass; const TreeDev* tree; SeqState st; KVCache kv; int kv_f32; float* Q; const float* rope_cos; const float* rope_sin; int H;
+  // EPI_RESID / EPI_SWIGLU
+  const float* h_in; float* h_out; const float* bias; const float* gain_next; bf16_t* xf_out; int xf_KS; float* ssq_out; int d;
+  // EPI_LOGITS
+  float* logits; int out_kind, V, only_last_row;
+};
+
+__device__ inline float pt_sum(const float* __restrict__ PT, int S, int Npad, int n, int m) {
+  float a = 0.f;
+  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + n) * 32 + m];
+  return a;
+}
+
+template <int NXP>
+__device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1) {
+  const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
+  const int dh = g.kv.head_dim, half = dh >> 1, KVH = g.kv.n_kv_heads, H = g.H;
+  const bool live = m < g.M;
+  RowInfo ri;
+  ri.valid = 0; ri.pos = 0; ri.seq = 0; ri.slot = 0;
+  if (live) ri = row_info(g.pass, g.tree, g.st, m);
+  const float rs = live ? row_rstd(g.in_scale, m) : 0.f;
+  const int npairs = (n1 - n0) >> 1;
+  for (int p = slot; p < npairs; p += V2_THREADS / 32) {
+    const int n = n0 + 2 * p, hd = n / dh, pr = n % dh;
+    float a = pt_sum(g.PT, g.S, g.Npad, n, m) * rs, b = pt_sum(g.PT, g.S, g.Npad, n + 1, m) * rs;
+    int d1, d2;
+    if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
+      const int i = pr >> 1;
+      const float c = g.rope_cos[(size_t)ri.pos * half + i], sn = g.rope_sin[(size_t)ri.pos * half + i];
+      const float a2 = a * c - b * sn, b2 = b * c + a * sn;
+      a = a2; b = b2; d1 = i; d2 = i + half;
+    } else { d1 = pr; d2 = pr + 1; }
+    if (!live) continue;
+    if (hd < H) {
+      float* q = g.Q + ((size_t)m * H + hd) * dh;
+      q[d1] = a; q[d2] = b;
+    } else if (ri.valid) {
+      const int kvh = (hd - H) % KVH;
+      const size_t off = kv_offset(g.kv, ri.seq, ri.slot, kvh);
+      void* base = hd < H + KVH ? g.kv.k : g.kv.v;
+      if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
+      else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
+    }
+  }
+}
+
+template <int NXP>
+__device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, float* sh /*>= 16*32 floats*/) {
+  const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
+  const bool live = m < g.M;
+  const int nchunks = (n1 - n0 + 7) >> 3;
+  float ss = 0.f;
+  for (int c = slot; c < nchunks; c += V2_THREADS / 32) {
+    const int n = n0 + 8 * c;
+    float x[8];
+    for (int t = 0; t < 8; ++t) {
+      float v = 0.f;
+      if (n + t < n1) {
+        v = pt_sum(g.PT, g.S, g.Npad, n + t, m);
+        if (g.bias) v += g.bias[n + t];
+        if (g.h_in && live) v += g.h_in[(size_t)m * g.d + n + t];
+        if (live) g.h_out[(size_t)m * g.d + n + t] = v;
+        ss += v * v;
+        x[t] = g.gain_next ? v * g.gain_next[n + t] : v;
+      } else x[t] = 0.f;
+    }
+    if (live) xf_store8(g.xf_out, m, n, 1, g.xf_KS, NXP, x);
+  }
+  __syncthreads();
+  sh[slot * 32 + m] = ss;
+  __syncthreads();
+  if (threadIdx.x < 32 && g.ssq_out) {
+    float a = 0.f;
+    for (int i = 0; i < V2_THREADS / 32; ++i) a += sh[i * 32 + threadIdx.x];
+    g.ssq_out[grp * 32 + threadIdx.x] = a;
+  }
+}
+
+template <int NXP>
+__device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1) {
+  const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
+  const bool live = m < g.M;
+  const float rs = live ? row_rstd(g.in_scale, m) : 0.f;
+  const int items = ((n1 - n0) >> 5) * 2;
+  for (int it = slot; it < items; it += V2_THREADS / 32) {
+    const int rb = it >> 1, c2 = it & 1;
+    const int nb = n0 + rb * 32 + 8 * c2;            // gate rows; the matching up rows are 16 further
+    const int f = ((n0 >> 5) + rb) * 16 + 8 * c2;
+    float x[8];
+    for (int t = 0; t < 8; ++t) {
+      const float gg = pt_sum(g.PT, g.S, g.Npad, nb + t, m) * rs, uu = pt_sum(g.PT, g.S, g.Npad, nb + 16 + t, m) * rs;
+      x[t] = gg / (1.0f + __expf(-gg)) * uu;
+    }
+    if (live) xf_store8(g.xf_out, m, f, 1, g.xf_KS, NXP, x);
+  }
+}
+
+__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/) {
+  const int a = threadIdx.x & 31, b = threadIdx.x >> 5;        // read side: m = a, row b of 16
+  const int a2 = threadIdx.x & 15, b2 = threadIdx.x >> 4;      // write side: n = a2, m = b2
+  const float rs = a < g.M ? row_rstd(g.in_scale, a) : 0.f;
+  long dst = -1;
+  if (b2 < g.M) {
+    RowInfo ri = row_info(g.pass, g.tree, g.st, b2);
+    if (ri.valid) {
+      if (g.out_kind == 0) { if (ri.node >= 0) dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
+      else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) dst = (long)ri.seq * g.V;
+    }
+  }
+  for (int nb = n0; nb < n1; nb += 16) {
+    const int n = nb + b;
+    sh[b * 33 + a] = (n < n1 && a < g.M) ? pt_sum(g.PT, g.S, g.Npad, n, a) * rs : 0.f;
+    __syncthreads();
+    if (dst >= 0 && nb + a2 < n1 && nb + a2 < g.V) g.logits[dst + nb + a2] = sh[a2 * 33 + b2];
+    __syncthreads();
+  }
+}
+
+template <int NWP, int NXP, int RW, int DEPTH>
+__global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float sh_small[16 * 33];
+  __shared__ int s_last;
+  u32x4* xs = (u32x4*)smem;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int s = blockIdx.x % g.S, grp = blockIdx.x / g.S;
+  const int rb0 = (int)((long)grp * g.NRB / g.groups), rb1 = (int)((long)(grp + 1) * g.NRB / g.groups);
+  const int ks0 = (int)((long)s * g.KS / g.S), ks1 = (int)((long)(s + 1) * g.KS / g.S), kt = ks1 - ks0;
+  const int la = w % g.lanes, kb_i = w / g.lanes;
+  const int kb = (int)((long)kb_i * kt / g.kparts), ke = (int)((long)(kb_i + 1) * kt / g.kparts);
+  int nr = 0;
+  for (int j = 0; j < RW; ++j) nr += (rb0 + la + j * g.lanes < rb1) ? 1 : 0;
+  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+
+  // stage this work-group's K slice of X: per plane a contiguous run of kt tiles
+  for (int p = 0; p < NXP; ++p) {
+    const u32x4* src = (const u32x4*)(g.XF + ((size_t)p * g.KS + ks0) * 512);
+    u32x4* dst = xs + (size_t)p * kt * 64;
+    for (int i = threadIdx.x; i < kt * 64; i += V2_THREADS) dst[i] = src[i];
+  }
+  f32x16 acc[RW];
+#pragma unroll
+  for (int j = 0; j < RW; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  const u32x4* wp[RW];
+#pragma unroll
+  for (int j = 0; j < RW; ++j) {
+    int rb = rb0 + la + j * g.lanes;
+    if (rb >= rb1) rb = rb0;                                  // never dereferenced: guarded by j < nr
+    wp[j] = (const u32x4*)(g.W + ((size_t)rb * g.KS + ks0) * 512) + lane;
+  }
+  u32x4 abuf[DEPTH][RW][NWP];
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd)
+    if (kb + dd < ke)
+#pragma unroll
+      for (int j = 0; j < RW; ++j)
+        if (j < nr)
+#pragma unroll
+          for (int p = 0; p < NWP; ++p)
+            abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)(kb + dd) * 64) + p * g.wps);
+  __syncthreads();
+  for (int k = kb; k < ke; k += DEPTH) {
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) {
+      const int kk = k + dd;
+      if (kk < ke) {
+        u32x4 bq[NXP];
+#pragma unroll
+        for (int q = 0; q < NXP; ++q) bq[q] = xs[((size_t)q * kt + kk) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < RW; ++j)
+          if (j < nr) {
+#pragma unroll
+            for (int p = 0; p < NWP; ++p)
+#pragma unroll
+              for (int q = 0; q < NXP; ++q)
+                if (p + q < PMAX)
+                  acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
+                                                                    __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
+            if (kk + DEPTH < ke) {
+#pragma unroll
+              for (int p = 0; p < NWP; ++p)
+                abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)(kk + DEPTH) * 64) + p * g.wps);
+            }
+          }
+      }
+    }
+  }
+  // waves that split K inside the work-group: sum through LDS in k-part order
+  if (g.kparts > 1) {
+    __syncthreads();                                          // the X slice is no longer needed
+    float* red = (float*)smem;
+    if (kb_i > 0) {
+#pragma unroll
+      for (int j = 0; j < RW; ++j)
+        if (j < nr)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            red[((((size_t)la * (g.kparts - 1) + (kb_i - 1)) * RW + j) * 16 + r) * 64 + lane] = acc[j][r];
+    }
+    __syncthreads();
+    if (kb_i == 0) {
+      for (int b = 1; b < g.kparts; ++b)
+#pragma unroll
+        for (int j = 0; j < RW; ++j)
+          if (j < nr)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              acc[j][r] += red[((((size_t)la * (g.kparts - 1) + (b - 1)) * RW + j) * 16 + r) * 64 + lane];
+    }
+  }
+  if (kb_i == 0) {
+#pragma unroll
+    for (int j = 0; j < RW; ++j)
+      if (j < nr) {
+        const int rb = rb0 + la + j * g.lanes;
+        float* out = g.PT + ((size_t)s * g.Npad + (size_t)rb * 32) * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 32 + (lane & 31)] = acc[j][r];
+      }
+  }
+  // publish the partials; the last work-group of this row group to arrive finishes the job
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == g.S - 1);
+    if (s_last) g.counters[grp] = 0;                           // ready for the next launch on this stream
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
+  if (n1 <= n0) return;
+  switch (g.epi) {
+    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1); break;
+    case EPI_RESID: epilogue_resid<NXP>(g, grp, n0, n1, sh_small); break;
+    case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1); break;
+    default: epilogue_logits(g, n0, n1, sh_small); break;
+  }
+}
+
+// Rows of a pass that need no GEMM in front: h = embedding of the row's token.  Writes h, XF(h * gain) and the
+// partial sums of squares, one column slab per block (the same outputs a residual epilogue produces).
+template <typename EmbT, int NXP>
+__global__ __launch_bounds__(256) void k2_embed(Pass pass, const TreeDev* tree, SeqState st, const int* tree_tok,
+                                                const EmbT* __restrict__ embed, int vocab, int M, int d, float* h,
+                                                const float* gain, bf16_t* xf_out, float* ssq_out) {
+  __shared__ float sh[8 * 32];
+  const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;          // 8 slots
+  const int grp = blockIdx.x, groups = gridDim.x;
+  const int c0 = (int)((long)grp * (d / 8) / groups), c1 = (int)((long)(grp + 1) * (d / 8) / groups);
+  const bool live = m < M;
+  int tok = 0;
+  if (live) {
+    RowInfo ri = row_info(pass, tree, st, m);
+    if (pass.kind == PASS_VERIFY) tok = tree_tok[ri.seq * tree->M + ri.node];
+    else tok = st.tokens[(size_t)ri.seq * st.tok_stride + ri.pos];
+    tok = min(max(tok, 0), vocab - 1);
+  }
+  float ss = 0.f;
+  for (int c = c0 + slot; c < c1; c += 8) {
+    float x[8];
+    for (int t = 0; t < 8; ++t) {
+      float v = 0.f;
+      if (live) {
+        if constexpr (sizeof(EmbT) == 4) v = ((const float*)embed)[(size_t)tok * d + 8 * c + t];
+        else v = bf16_to_f32(((const bf16_t*)embed)[(size_t)tok * d + 8 * c + t]);
+        h[(size_t)m * d + 8 * c + t] = v;
+      }
+      ss += v * v;
+      x[t] = v * gain[8 * c + t];
+    }
+    if (live) xf_store8(xf_out, m, 8 * c, 1, d / 16, NXP, x);
+  }
+  sh[slot * 32 + m] = ss;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    float a = 0.f;
+    for (int i = 0; i < 8; ++i) a += sh[i * 32 + threadIdx.x];
+    ssq_out[grp * 32 + threadIdx.x] = a;
+  }
+}
+
+// features[m][k] = h[m][k] * rstd[m] * gain[k]   (the target's final RMSNorm, Sec. 2: f is what the LM head reads)
+__global__ __launch_bounds__(256) void k2_features(const float* h, RowScale rs, const float* gain, int M, int d, float* out) {
+  const int m = blockIdx.x;
+  if (m >= M) return;
+  const float r = row_rstd(rs, m);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) out[(size_t)m * d + k] = h[(size_t)m * d + k] * r * gain[k];
+}
+
+// ============================================================================ tree-masked paged attention, <= 32 rows per sequence
+// Block = (kv split, query head, sequence).  Same masking rule as k_attn; K/V rows are read with 16-byte loads,
+// the PV product keeps a 4x4 register tile per thread, and the last split to finish merges all splits of its
+// (sequence, head) and writes the result in XF layout for the output projection.
+template <typename CT, int DH>
+__global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
+                                               const float* __restrict__ Q, float* part_o, float* part_ml, int H,
+                                               int n_splits, int n_new, float scale, int* counters, bf16_t* xf_out,
+                                               int nplanes) {
+  constexpr int D4 = DH / 4;                // float4 chunks per row
+  constexpr int NRG = 256 / D4;             // row groups in the PV phase
+  constexpr int RPT = (32 + NRG - 1) / NRG; // rows per thread in the PV phase
+  __shared__ __attribute__((aligned(16))) float q_s[32][DH];
+  __shared__ float s_s[32][64];
+  __shared__ float alpha_s[32], m_s[32], l_s[32];
+  __shared__ int rel_s[32], causal_s[32];
+  __shared__ unsigned long long mask_s[32];
+  __shared__ int s_last;
+  const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z;
+  const int r0 = seq_l * pass.rows_per_seq;
+  const int R = min(32, pass.rows_per_seq);
+  const int kvh = hd / (H / kv.n_kv_heads);
+  const int tid = threadIdx.x;
+  RowInfo r_first = row_info(pass, tree, st, r0);
+  const int seq = r_first.seq, base = r_first.base;
+  if (tid < 32) {
+    if (tid < R) {
+      RowInfo ri = row_info(pass, tree, st, r0 + tid);
+      rel_s[tid] = ri.rel; causal_s[tid] = ri.causal; mask_s[tid] = ri.mask;
+    }
+    m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f;
+  }
+  for (int i = tid; i < R * DH; i += 256) q_s[i / DH][i % DH] = Q[((size_t)(r0 + i / DH) * H + hd) * DH + i % DH] * scale;
+  const int T = base + n_new;
+  // the split boundaries depend on `base` only, so a row sees the same partition whatever else is in the pass
+  const int tps = ((base + 64 + n_splits - 1) / n_splits + 63) / 64 * 64;
+  const int t_begin = split * tps, t_end = min(T, t_begin + tps);
+  f32x4 acc[RPT];
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int d4 = tid % D4, rg = tid / D4;
+  __syncthreads();
+  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+    {   // scores: thread = (token tl, row quarter rq)
+      const int tl = tid & 63, rq = tid >> 6;
+      const int t = t0 + tl;
+      if (t < t_end) {
+        const CT* kp = (const CT*)kv.k + kv_offset(kv, seq, t, kvh);
+        f32x4 kr[D4];
+        if constexpr (sizeof(CT) == 4) {
+#pragma unroll
+          for (int c = 0; c < D4; ++c) kr[c] = *(const f32x4*)((const float*)kp + 4 * c);
+        } else {
+#pragma unroll
+          for (int c = 0; c < D4; c += 2) {
+            u32x4 raw = *(const u32x4*)((const bf16_t*)kp + 4 * c);
+            kr[c] = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
+                          __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
+            kr[c + 1] = f32x4{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xFFFF0000u),
+                              __builtin_bit_cast(float, raw.w << 16), __builtin_bit_cast(float, raw.w & 0xFFFF0000u)};
+          }
+        }
+        for (int r = rq; r < R; r += 4) {
+          f32x4 sd = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int c = 0; c < D4; ++c) sd += *(const f32x4*)&q_s[r][4 * c] * kr[c];
+          bool vis = t < base;
+          if (!vis) {
+            int j = t - base;
+            vis = causal_s[r] ? (j <= rel_s[r]) : (j < 64 && ((mask_s[r] >> j) & 1ull));
+          }
+          s_s[r][tl] = vis ? (sd.x + sd.y) + (sd.z + sd.w) : -INFINITY;
+        }
+      } else {
+        for (int r = rq; r < R; r += 4) s_s[r][tl] = -INFINITY;
+      }
+    }
+    __syncthreads();
+    {   // running max / sum: wave w handles rows w, w+4, ...; lane = token
+      const int lane = tid & 63, w = tid >> 6;
+      for (int r = w; r < R; r += 4) {
+        float sv = s_s[r][lane];
+        float mx = wave_max(sv);
+        float m_old = m_s[r];
+        float m_new = fmaxf(m_old, mx);
+        float p = (m_new == -INFINITY) ? 0.f : __expf(sv - m_new);
+        float al = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
+        float ps = wave_sum(p);
+        s_s[r][lane] = p;
+        if (lane == 0) { m_s[r] = m_new; l_s[r] = l_s[r] * al + ps; alpha_s[r] = al; }
+      }
+    }
+    __syncthreads();
+    {   // acc = acc*alpha + P.V : thread = (float4 column d4, row group rg)
+      const int nt = min(64, t_end - t0);
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        int r = rg + i * NRG;
+        if (r < R) acc[i] *= alpha_s[r];
+      }
+      for (int tl = 0; tl < nt; ++tl) {
+        const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
+        f32x4 vv;
+        if constexpr (sizeof(CT) == 4) vv = *(const f32x4*)((const float*)vp + 4 * d4);
+        else {
+          const uint2 raw = *(const uint2*)((const bf16_t*)vp + 4 * d4);
+          vv = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
+                     __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
+        }
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          int r = rg + i * NRG;
+          if (r < R) acc[i] += s_s[r][tl] * vv;
+        }
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    int r = rg + i * NRG;
+    if (r < R) *(f32x4*)(part_o + (((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + 4 * d4) = acc[i];
+  }
+  if (tid < R) {
+    size_t o = (((size_t)(r0 + tid) * H + hd) * n_splits + split) * 2;
+    part_ml[o] = m_s[tid];
+    part_ml[o + 1] = l_s[tid];
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    int* cnt = counters + seq_l * H + hd;
+    int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == n_splits - 1);
+    if (s_last) *cnt = 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  // merge the splits of (sequence, head): thread = (row, 8-wide column chunk)
+  const int KS = H * DH / 16;
+  for (int it = tid; it < R * (DH / 8); it += 256) {
+    const int r = it / (DH / 8), d0 = (it % (DH / 8)) * 8;
+    const float* ml = part_ml + ((size_t)(r0 + r) * H + hd) * n_splits * 2;
+    float mm = -INFINITY;
+    for (int sp = 0; sp < n_splits; ++sp) mm = fmaxf(mm, ml[2 * sp]);
+    float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int sp = 0; sp < n_splits; ++sp) {
+      const float ms = ml[2 * sp];
+      if (ms == -INFINITY) continue;
+      const float wgt = __expf(ms - mm);
+      den += wgt * ml[2 * sp + 1];
+      const float* o = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + sp) * DH + d0;
+      for (int t = 0; t < 8; ++t) x[t] += wgt * o[t];
+    }
+    const float inv = den > 0.f ? 1.0f / den : 0.f;
+    for (int t = 0; t < 8; ++t) x[t] *= inv;
+    xf_store8(xf_out, r0 + r, hd * DH + d0, 1, KS, nplanes, x);
+  }
+}
