@@ -14,6 +14,13 @@
 
 #define V2_THREADS 512
 
+// Data that one work-group writes and another reads INSIDE one kernel (split-K partials, attention partials) goes
+// through agent-scope relaxed atomics: such stores are written through to the device-coherent level and such
+// loads never hit a stale line of another XCD's L2, so no cache write-back / invalidate is needed around the
+// arrival counter -- a work-group-scope fence (a wait for the stores to be acknowledged) is enough.
+__device__ inline void coh_store(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ inline float coh_load(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 struct RowScale {            // 1/rms of the rows that produced the GEMM input; ssq == nullptr -> 1
   const float* ssq;          // [groups][32] partial sums of squares
   int groups;
@@ -22,7 +29,15 @@ struct RowScale {            // 1/rms of the rows that produced the GEMM input; 
 __device__ inline float row_rstd(const RowScale& rs, int m) {
   if (!rs.ssq) return 1.0f;
   float a = 0.f;
-  for (int g = 0; g < rs.groups; ++g) a += rs.ssq[g * 32 + m];
+  int g = 0;
+  for (; g + 8 <= rs.groups; g += 8) {                 // 8 loads in flight, summed in group order
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = rs.ssq[(g + i) * 32 + m];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a += v[i];
+  }
+  for (; g < rs.groups; ++g) a += rs.ssq[g * 32 + m];
   return 1.0f / sqrtf(a * rs.inv_d + rs.eps);
 }
 
@@ -43,10 +58,19 @@ struct Gemm2 {
   float* logits; int out_kind, V, only_last_row;
 };
 
-__device__ inline float pt_sum(const float* __restrict__ PT, int S, int Npad, int n, int m) {
-  float a = 0.f;
-  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + n) * 32 + m];
-  return a;
+// out[t] = sum over the K splits of PT[s][rows[t]][m], t < 8: eight coherent loads in flight per split, splits
+// added in order (the loads are agent-scope atomics, which the compiler will not hoist above one another's uses
+// unless they are issued together like this).
+__device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) out[t] = 0.f;
+  for (int s = 0; s < S; ++s) {
+    float v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = coh_load(PT + ((size_t)s * Npad + rows[t]) * 32 + m);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) out[t] += v[t];
+  }
 }
 
 template <int NXP>
@@ -59,26 +83,38 @@ __device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1) {
   if (live) ri = row_info(g.pass, g.tree, g.st, m);
   const float rs = live ? row_rstd(g.in_scale, m) : 0.f;
   const int npairs = (n1 - n0) >> 1;
-  for (int p = slot; p < npairs; p += V2_THREADS / 32) {
-    const int n = n0 + 2 * p, hd = n / dh, pr = n % dh;
-    float a = pt_sum(g.PT, g.S, g.Npad, n, m) * rs, b = pt_sum(g.PT, g.S, g.Npad, n + 1, m) * rs;
-    int d1, d2;
-    if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
-      const int i = pr >> 1;
-      const float c = g.rope_cos[(size_t)ri.pos * half + i], sn = g.rope_sin[(size_t)ri.pos * half + i];
-      const float a2 = a * c - b * sn, b2 = b * c + a * sn;
-      a = a2; b = b2; d1 = i; d2 = i + half;
-    } else { d1 = pr; d2 = pr + 1; }
-    if (!live) continue;
-    if (hd < H) {
-      float* q = g.Q + ((size_t)m * H + hd) * dh;
-      q[d1] = a; q[d2] = b;
-    } else if (ri.valid) {
-      const int kvh = (hd - H) % KVH;
-      const size_t off = kv_offset(g.kv, ri.seq, ri.slot, kvh);
-      void* base = hd < H + KVH ? g.kv.k : g.kv.v;
-      if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
-      else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
+  constexpr int SL = V2_THREADS / 32;
+  for (int p0 = slot; p0 < npairs; p0 += 4 * SL) {          // four pairs (eight rows) per batch
+    int rows[8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int p = min(p0 + u * SL, npairs - 1);
+      rows[2 * u] = n0 + 2 * p; rows[2 * u + 1] = n0 + 2 * p + 1;
+    }
+    float val[8];
+    pt_sum8(g.PT, g.S, g.Npad, rows, m, val);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u * SL >= npairs || !live) continue;
+      const int n = rows[2 * u], hd = n / dh, pr = n % dh;
+      float a = val[2 * u] * rs, b = val[2 * u + 1] * rs;
+      int d1, d2;
+      if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
+        const int i = pr >> 1;
+        const float c = g.rope_cos[(size_t)ri.pos * half + i], sn = g.rope_sin[(size_t)ri.pos * half + i];
+        const float a2 = a * c - b * sn, b2 = b * c + a * sn;
+        a = a2; b = b2; d1 = i; d2 = i + half;
+      } else { d1 = pr; d2 = pr + 1; }
+      if (hd < H) {
+        float* q = g.Q + ((size_t)m * H + hd) * dh;
+        q[d1] = a; q[d2] = b;
+      } else if (ri.valid) {
+        const int kvh = (hd - H) % KVH;
+        const size_t off = kv_offset(g.kv, ri.seq, ri.slot, kvh);
+        void* base = hd < H + KVH ? g.kv.k : g.kv.v;
+        if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
+        else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
+      }
     }
   }
 }
@@ -91,11 +127,16 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
   float ss = 0.f;
   for (int c = slot; c < nchunks; c += V2_THREADS / 32) {
     const int n = n0 + 8 * c;
-    float x[8];
+    float x[8], pv[8];
+    int rows[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) rows[t] = min(n + t, n1 - 1);
+    pt_sum8(g.PT, g.S, g.Npad, rows, m, pv);
+#pragma unroll
     for (int t = 0; t < 8; ++t) {
       float v = 0.f;
       if (n + t < n1) {
-        v = pt_sum(g.PT, g.S, g.Npad, n + t, m);
+        v = pv[t];
         if (g.bias) v += g.bias[n + t];
         if (g.h_in && live) v += g.h_in[(size_t)m * g.d + n + t];
         if (live) g.h_out[(size_t)m * g.d + n + t] = v;
@@ -125,9 +166,15 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1) {
     const int rb = it >> 1, c2 = it & 1;
     const int nb = n0 + rb * 32 + 8 * c2;            // gate rows; the matching up rows are 16 further
     const int f = ((n0 >> 5) + rb) * 16 + 8 * c2;
-    float x[8];
+    float x[8], gv[8], uv[8];
+    int rg_[8], ru_[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { rg_[t] = nb + t; ru_[t] = nb + 16 + t; }
+    pt_sum8(g.PT, g.S, g.Npad, rg_, m, gv);
+    pt_sum8(g.PT, g.S, g.Npad, ru_, m, uv);
+#pragma unroll
     for (int t = 0; t < 8; ++t) {
-      const float gg = pt_sum(g.PT, g.S, g.Npad, nb + t, m) * rs, uu = pt_sum(g.PT, g.S, g.Npad, nb + 16 + t, m) * rs;
+      const float gg = gv[t] * rs, uu = uv[t] * rs;
       x[t] = gg / (1.0f + __expf(-gg)) * uu;
     }
     if (live) xf_store8(g.xf_out, m, f, 1, g.xf_KS, NXP, x);
@@ -146,13 +193,88 @@ __device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh
       else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) dst = (long)ri.seq * g.V;
     }
   }
-  for (int nb = n0; nb < n1; nb += 16) {
-    const int n = nb + b;
-    sh[b * 33 + a] = (n < n1 && a < g.M) ? pt_sum(g.PT, g.S, g.Npad, n, a) * rs : 0.f;
-    __syncthreads();
-    if (dst >= 0 && nb + a2 < n1 && nb + a2 < g.V) g.logits[dst + nb + a2] = sh[a2 * 33 + b2];
-    __syncthreads();
+  for (int nb0 = n0; nb0 < n1; nb0 += 128) {                 // 8 x 16 rows per batch of loads
+    int rows[8];
+    float val[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rows[i] = min(nb0 + 16 * i + b, n1 - 1);
+    pt_sum8(g.PT, g.S, g.Npad, rows, a, val);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int nb = nb0 + 16 * i;
+      sh[b * 33 + a] = (nb + b < n1 && a < g.M) ? val[i] * rs : 0.f;
+      __syncthreads();
+      if (dst >= 0 && nb + a2 < n1 && nb + a2 < g.V) g.logits[dst + nb + a2] = sh[a2 * 33 + b2];
+      __syncthreads();
+    }
   }
+}
+
+template <int NWP, int NXP, int NR, int DEPTH>
+__device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, int kb, int ke, const u32x4* const* wp,
+                                          size_t wps, f32x16* acc, int lane) {
+  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+  if (ke <= kb) return;
+  u32x4 abuf[DEPTH][NR][NWP];
+  const int klast = ke - 1;
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) {
+    const int kk = min(kb + dd, klast);
+#pragma unroll
+    for (int j = 0; j < NR; ++j)
+#pragma unroll
+      for (int p = 0; p < NWP; ++p) abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
+  }
+  int k = kb;
+  for (; k + DEPTH < ke; k += DEPTH) {
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) {
+      const int kk = k + dd;
+      u32x4 bq[NXP];
+#pragma unroll
+      for (int q = 0; q < NXP; ++q) bq[q] = xs[((size_t)q * kt + kk) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p)
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            if (p + q < PMAX)
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
+                                                                __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
+      const int kn = min(kk + DEPTH, klast);
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p) abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kn * 64) + p * wps);
+      __builtin_amdgcn_sched_barrier(0);          // keep "use a slot, refill that slot" in program order
+    }
+  }
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) {
+    const int kk = k + dd;
+    if (kk < ke) {
+      u32x4 bq[NXP];
+#pragma unroll
+      for (int q = 0; q < NXP; ++q) bq[q] = xs[((size_t)q * kt + kk) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p)
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            if (p + q < PMAX)
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
+                                                                __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
+    }
+  }
+}
+
+template <int NWP, int NXP, int RW, int NR, int DEPTH>
+__device__ __forceinline__ void k2_stream_dispatch(int nr, const u32x4* xs, int kt, int kb, int ke, const u32x4* const* wp,
+                                                   size_t wps, f32x16* acc, int lane) {
+  if (nr == NR) k2_stream<NWP, NXP, NR, DEPTH>(xs, kt, kb, ke, wp, wps, acc, lane);
+  else if constexpr (NR > 1) k2_stream_dispatch<NWP, NXP, RW, NR - 1, DEPTH>(nr, xs, kt, kb, ke, wp, wps, acc, lane);
 }
 
 template <int NWP, int NXP, int RW, int DEPTH>
@@ -169,13 +291,22 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   const int kb = (int)((long)kb_i * kt / g.kparts), ke = (int)((long)(kb_i + 1) * kt / g.kparts);
   int nr = 0;
   for (int j = 0; j < RW; ++j) nr += (rb0 + la + j * g.lanes < rb1) ? 1 : 0;
-  constexpr int PMAX = NWP > NXP ? NWP : NXP;
 
-  // stage this work-group's K slice of X: per plane a contiguous run of kt tiles
+  // stage this work-group's K slice of X: per plane a contiguous run of kt tiles (8 loads in flight per thread)
   for (int p = 0; p < NXP; ++p) {
     const u32x4* src = (const u32x4*)(g.XF + ((size_t)p * g.KS + ks0) * 512);
     u32x4* dst = xs + (size_t)p * kt * 64;
-    for (int i = threadIdx.x; i < kt * 64; i += V2_THREADS) dst[i] = src[i];
+    const int n = kt * 64;
+    for (int i0 = 0; i0 < n; i0 += V2_THREADS * 8) {
+      u32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[min(i0 + u * V2_THREADS + (int)threadIdx.x, n - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * V2_THREADS + (int)threadIdx.x;
+        if (i < n) dst[i] = v[u];
+      }
+    }
   }
   f32x16 acc[RW];
 #pragma unroll
@@ -186,47 +317,11 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
 #pragma unroll
   for (int j = 0; j < RW; ++j) {
     int rb = rb0 + la + j * g.lanes;
-    if (rb >= rb1) rb = rb0;                                  // never dereferenced: guarded by j < nr
+    if (rb >= rb1) rb = rb0;                                  // never dereferenced: only the first nr entries are used
     wp[j] = (const u32x4*)(g.W + ((size_t)rb * g.KS + ks0) * 512) + lane;
   }
-  u32x4 abuf[DEPTH][RW][NWP];
-#pragma unroll
-  for (int dd = 0; dd < DEPTH; ++dd)
-    if (kb + dd < ke)
-#pragma unroll
-      for (int j = 0; j < RW; ++j)
-        if (j < nr)
-#pragma unroll
-          for (int p = 0; p < NWP; ++p)
-            abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)(kb + dd) * 64) + p * g.wps);
   __syncthreads();
-  for (int k = kb; k < ke; k += DEPTH) {
-#pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd) {
-      const int kk = k + dd;
-      if (kk < ke) {
-        u32x4 bq[NXP];
-#pragma unroll
-        for (int q = 0; q < NXP; ++q) bq[q] = xs[((size_t)q * kt + kk) * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < RW; ++j)
-          if (j < nr) {
-#pragma unroll
-            for (int p = 0; p < NWP; ++p)
-#pragma unroll
-              for (int q = 0; q < NXP; ++q)
-                if (p + q < PMAX)
-                  acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
-                                                                    __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
-            if (kk + DEPTH < ke) {
-#pragma unroll
-              for (int p = 0; p < NWP; ++p)
-                abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)(kk + DEPTH) * 64) + p * g.wps);
-            }
-          }
-      }
-    }
-  }
+  k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane);
   // waves that split K inside the work-group: sum through LDS in k-part order
   if (g.kparts > 1) {
     __syncthreads();                                          // the X slice is no longer needed
@@ -257,20 +352,20 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
         const int rb = rb0 + la + j * g.lanes;
         float* out = g.PT + ((size_t)s * g.Npad + (size_t)rb * 32) * 32;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 32 + (lane & 31)] = acc[j][r];
+        for (int r = 0; r < 16; ++r) coh_store(out + (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 32 + (lane & 31), acc[j][r]);
       }
   }
   // publish the partials; the last work-group of this row group to arrive finishes the job
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // every coherent store above has been acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
-    int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == g.S - 1);
-    if (s_last) g.counters[grp] = 0;                           // ready for the next launch on this stream
+    if (s_last) __hip_atomic_store(g.counters + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
   if (n1 <= n0) return;
   switch (g.epi) {
@@ -431,19 +526,28 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
         int r = rg + i * NRG;
         if (r < R) acc[i] *= alpha_s[r];
       }
-      for (int tl = 0; tl < nt; ++tl) {
-        const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
-        f32x4 vv;
-        if constexpr (sizeof(CT) == 4) vv = *(const f32x4*)((const float*)vp + 4 * d4);
-        else {
-          const uint2 raw = *(const uint2*)((const bf16_t*)vp + 4 * d4);
-          vv = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
-                     __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
+      for (int tb = 0; tb < nt; tb += 8) {               // 8 V rows in flight per thread
+        f32x4 vv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int tl = min(tb + u, nt - 1);
+          const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
+          if constexpr (sizeof(CT) == 4) vv[u] = *(const f32x4*)((const float*)vp + 4 * d4);
+          else {
+            const uint2 raw = *(const uint2*)((const bf16_t*)vp + 4 * d4);
+            vv[u] = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
+                          __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
+          }
         }
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) {
-          int r = rg + i * NRG;
-          if (r < R) acc[i] += s_s[r][tl] * vv;
+        for (int u = 0; u < 8; ++u) {
+          if (tb + u < nt) {
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+              int r = rg + i * NRG;
+              if (r < R) acc[i] += s_s[r][tb + u] * vv[u];
+            }
+          }
         }
       }
     }
@@ -452,39 +556,66 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     int r = rg + i * NRG;
-    if (r < R) *(f32x4*)(part_o + (((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + 4 * d4) = acc[i];
+    if (r < R) {
+      float* po = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + 4 * d4;
+      coh_store(po, acc[i].x); coh_store(po + 1, acc[i].y); coh_store(po + 2, acc[i].z); coh_store(po + 3, acc[i].w);
+    }
   }
   if (tid < R) {
     size_t o = (((size_t)(r0 + tid) * H + hd) * n_splits + split) * 2;
-    part_ml[o] = m_s[tid];
-    part_ml[o + 1] = l_s[tid];
+    coh_store(part_ml + o, m_s[tid]);
+    coh_store(part_ml + o + 1, l_s[tid]);
   }
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
     int* cnt = counters + seq_l * H + hd;
-    int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == n_splits - 1);
-    if (s_last) *cnt = 0;
+    if (s_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   // merge the splits of (sequence, head): thread = (row, 8-wide column chunk)
   const int KS = H * DH / 16;
   for (int it = tid; it < R * (DH / 8); it += 256) {
     const int r = it / (DH / 8), d0 = (it % (DH / 8)) * 8;
     const float* ml = part_ml + ((size_t)(r0 + r) * H + hd) * n_splits * 2;
+    float msv[16], lsv[16];
+#pragma unroll
+    for (int sp = 0; sp < 16; ++sp) {                          // all (max, sum) pairs in flight at once
+      const int q = min(sp, n_splits - 1);
+      msv[sp] = coh_load(ml + 2 * q);
+      lsv[sp] = coh_load(ml + 2 * q + 1);
+    }
     float mm = -INFINITY;
-    for (int sp = 0; sp < n_splits; ++sp) mm = fmaxf(mm, ml[2 * sp]);
+#pragma unroll
+    for (int sp = 0; sp < 16; ++sp) if (sp < n_splits) mm = fmaxf(mm, msv[sp]);
     float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int sp = 0; sp < n_splits; ++sp) {
-      const float ms = ml[2 * sp];
-      if (ms == -INFINITY) continue;
-      const float wgt = __expf(ms - mm);
-      den += wgt * ml[2 * sp + 1];
-      const float* o = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + sp) * DH + d0;
-      for (int t = 0; t < 8; ++t) x[t] += wgt * o[t];
+    float wv[16];
+#pragma unroll
+    for (int sp = 0; sp < 16; ++sp) {
+      wv[sp] = (sp < n_splits && msv[sp] != -INFINITY) ? __expf(msv[sp] - mm) : 0.f;
+      den += wv[sp] * lsv[sp];
+    }
+    for (int sp0 = 0; sp0 < n_splits; sp0 += 4) {              // 4 splits x 8 values in flight, added in split order
+      float ov[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int q = min(sp0 + u, n_splits - 1);
+        const float* o = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + q) * DH + d0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) ov[u][t] = coh_load(o + t);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float wgt = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) if (q == sp0 + u) wgt = wv[q];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] += wgt * ov[u][t];
+      }
     }
     const float inv = den > 0.f ? 1.0f / den : 0.f;
     for (int t = 0; t < 8; ++t) x[t] *= inv;
