@@ -181,7 +181,7 @@ static int check_cfg(const eagle_config* c) {
   if (c->n_experts < 0 || c->n_experts > 64 || (c->n_experts > 0 && (c->experts_per_tok < 1 || c->experts_per_tok > c->n_experts || c->experts_per_tok > 4)))
     return fail(EAGLE_EINVAL, "bad expert counts");
   if (c->max_batch < 1 || c->max_batch > 64) return fail(EAGLE_EINVAL, "max_batch must be 1..64");
-  if (c->page_tokens < 16 || (c->page_tokens & (c->page_tokens - 1))) return fail(EAGLE_EINVAL, "page_tokens must be a power of two >= 16");
+  if (c->page_tokens < 32 || (c->page_tokens & (c->page_tokens - 1))) return fail(EAGLE_EINVAL, "page_tokens must be a power of two >= 32");
   if (c->max_seq < c->n_nodes + 2) return fail(EAGLE_EINVAL, "max_seq too small for the tree");
   if (!(c->temperature >= 0.f)) return fail(EAGLE_EINVAL, "temperature must be >= 0");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(EAGLE_EINVAL, "bad rms_eps / rope_theta");
@@ -709,11 +709,20 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   g.epi = EPI_QKV; g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups); g.kv = kv_for(c, li);
   if ((rc = gemm2(c, w.qkv, c->xf2_d, g, nullptr))) return rc;
   {
-    int n_splits = std::max(1, std::min(16, (ctx_max + 64 + 63) / 64));
+    int n_splits = std::max(1, std::min(16, (ctx_max + 64 + 127) / 128));   // 128 tokens = one 32-token block per wave
     dim3 grid(n_splits, H, pass.n_seq);
     float scale = 1.0f / std::sqrt((float)dh);
     KVCache kv = kv_for(c, li);
-#define ATTN2(CT, DH) k2_attn<CT, DH><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP)
+#define ATTN2(CT, DH)                                                                                                   \
+  do {                                                                                                                  \
+    static bool attr_done = false;                                                                                      \
+    if (!attr_done) {                                                                                                   \
+      HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); \
+      attr_done = true;                                                                                                 \
+    }                                                                                                                   \
+    k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
+        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP); \
+  } while (0)
     if (c->kv_f32) { if (dh == 128) ATTN2(float, 128); else if (dh == 64) ATTN2(float, 64); else ATTN2(float, 32); }
     else { if (dh == 128) ATTN2(bf16_t, 128); else if (dh == 64) ATTN2(bf16_t, 64); else ATTN2(bf16_t, 32); }
 #undef ATTN2

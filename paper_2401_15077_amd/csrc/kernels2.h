@@ -427,144 +427,213 @@ __global__ __launch_bounds__(256) void k2_features(const float* h, RowScale rs, 
 }
 
 // ============================================================================ tree-masked paged attention, <= 32 rows per sequence
-// Block = (kv split, query head, sequence).  Same masking rule as k_attn; K/V rows are read with 16-byte loads,
-// the PV product keeps a 4x4 register tile per thread, and the last split to finish merges all splits of its
-// (sequence, head) and writes the result in XF layout for the output projection.
+// Block = (kv split, query head, sequence), 4 waves.  Each wave runs flash attention on its own 32-token blocks
+// entirely in registers on the MFMA units:
+//   S^T[tok][q] = K[tok][:] . Q[q][:]      A = K block (32 tokens x 16 dims per step), B = Q fragments (kept in VGPRs)
+//   O^T[d][q]  += V[tok][d] * P[q][tok]    A = V^T (gathered so that the token order matches the S^T accumulator
+//                                          layout), B = P straight out of the accumulator registers
+// fp32 cache values and probabilities are split into bf16 hi + lo on the fly (hi*hi + hi*lo + lo*hi), so the
+// result keeps ~16 mantissa bits.  A lane always owns one query (column l%32): running max / sum and the rescale
+// of O^T are lane-local, the only cross-lane traffic is one xor-32 shuffle per reduction.  Keys: cache slots
+// [0, base) are visible to every row; slot base+j is visible iff bit j of the row's ancestor mask is set (tree
+// passes) or j <= the row's own relative index (causal passes).  Waves are merged through LDS, splits through
+// coherent partials and the last split to arrive, which writes XF layout for the output projection.
+__device__ inline void split8(const float* x, bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    hi[i] = (__bf16)x[i];
+    lo[i] = (__bf16)(x[i] - (float)hi[i]);
+  }
+}
+__device__ inline void load8(const float* p, float* x) {
+  const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ inline void load8(const bf16_t* p, float* x) {
+  const u32x4 r = *(const u32x4*)p;
+  x[0] = __builtin_bit_cast(float, r.x << 16); x[1] = __builtin_bit_cast(float, r.x & 0xFFFF0000u);
+  x[2] = __builtin_bit_cast(float, r.y << 16); x[3] = __builtin_bit_cast(float, r.y & 0xFFFF0000u);
+  x[4] = __builtin_bit_cast(float, r.z << 16); x[5] = __builtin_bit_cast(float, r.z & 0xFFFF0000u);
+  x[6] = __builtin_bit_cast(float, r.w << 16); x[7] = __builtin_bit_cast(float, r.w & 0xFFFF0000u);
+}
+
 template <typename CT, int DH>
 __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
                                                const float* __restrict__ Q, float* part_o, float* part_ml, int H,
                                                int n_splits, int n_new, float scale, int* counters, bf16_t* xf_out,
                                                int nplanes) {
-  constexpr int D4 = DH / 4;                // float4 chunks per row
-  constexpr int NRG = 256 / D4;             // row groups in the PV phase
-  constexpr int RPT = (32 + NRG - 1) / NRG; // rows per thread in the PV phase
-  __shared__ __attribute__((aligned(16))) float q_s[32][DH];
-  __shared__ float s_s[32][64];
-  __shared__ float alpha_s[32], m_s[32], l_s[32];
-  __shared__ int rel_s[32], causal_s[32];
-  __shared__ unsigned long long mask_s[32];
+  constexpr int KSN = DH / 16;              // k-steps of the QK product
+  constexpr int DB = DH / 32;               // 32-wide blocks of the head dimension
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_a[];
+  float* o_s = (float*)smem_a;              // [4 waves][DH][32]
+  float* ml_s = o_s + 4 * DH * 32;          // [4 waves][2][32]
   __shared__ int s_last;
   const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z;
   const int r0 = seq_l * pass.rows_per_seq;
   const int R = min(32, pass.rows_per_seq);
   const int kvh = hd / (H / kv.n_kv_heads);
-  const int tid = threadIdx.x;
-  RowInfo r_first = row_info(pass, tree, st, r0);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int q = lane & 31, hh = lane >> 5;
+  const RowInfo r_first = row_info(pass, tree, st, r0);
   const int seq = r_first.seq, base = r_first.base;
-  if (tid < 32) {
-    if (tid < R) {
-      RowInfo ri = row_info(pass, tree, st, r0 + tid);
-      rel_s[tid] = ri.rel; causal_s[tid] = ri.causal; mask_s[tid] = ri.mask;
-    }
-    m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f;
+  // this lane's query row
+  int rel = 0, causal = 1;
+  unsigned long long mask = 0ull;
+  if (q < R) {
+    const RowInfo ri = row_info(pass, tree, st, r0 + q);
+    rel = ri.rel; causal = ri.causal; mask = ri.mask;
   }
-  for (int i = tid; i < R * DH; i += 256) q_s[i / DH][i % DH] = Q[((size_t)(r0 + i / DH) * H + hd) * DH + i % DH] * scale;
+  bf16x8 qh[KSN], ql[KSN];
+#pragma unroll
+  for (int ks = 0; ks < KSN; ++ks) {
+    float x[8];
+    if (q < R) {
+      load8(Q + ((size_t)(r0 + q) * H + hd) * DH + 16 * ks + 8 * hh, x);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] *= scale;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] = 0.f;
+    }
+    split8(x, qh[ks], ql[ks]);
+  }
   const int T = base + n_new;
   // the split boundaries depend on `base` only, so a row sees the same partition whatever else is in the pass
   const int tps = ((base + 64 + n_splits - 1) / n_splits + 63) / 64 * 64;
   const int t_begin = split * tps, t_end = min(T, t_begin + tps);
-  f32x4 acc[RPT];
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 oacc[DB];
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int d4 = tid % D4, rg = tid / D4;
+  for (int b = 0; b < DB; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[b][r] = 0.f;
+
+  for (int tok0 = t_begin + 32 * w; tok0 < t_end; tok0 += 128) {   // wave w takes every 4th 32-token block
+    // a 32-token block starts on a multiple of 32 and therefore lies inside one 64-token (or larger) page
+    const size_t blk = kv_offset(kv, seq, tok0, kvh);
+    const CT* kp = (const CT*)kv.k + blk + (size_t)(lane & 31) * DH + 8 * hh;
+    const CT* vp = (const CT*)kv.v + blk;
+    float kx[KSN][8];
+#pragma unroll
+    for (int ks = 0; ks < KSN; ++ks) load8(kp + 16 * ks, kx[ks]);
+    f32x16 sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KSN; ++ks) {
+      bf16x8 kh, kl;
+      split8(kx[ks], kh, kl);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[ks], sacc, 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[ks], sacc, 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[ks], sacc, 0, 0, 0);
+    }
+    // V gathers go out before the softmax arithmetic: slot t of lane-half hh in k-step j is the token that
+    // accumulator register 8j+t of the same lane-half holds
+    float vx[2][DB][8];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int tl = 16 * j + 8 * (t >> 2) + 4 * hh + (t & 3);
+          vx[j][b][t] = cache_load(vp + (size_t)tl * DH + 32 * b + (lane & 31));
+        }
+    // mask, running max and sum for this lane's query
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int t = tok0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+      bool vis = t < base;
+      if (!vis) {
+        const int j = t - base;
+        vis = causal ? (j <= rel) : (j < 64 && ((mask >> j) & 1ull));
+      }
+      vis = vis && t < t_end && q < R;
+      sacc[r] = vis ? sacc[r] : -INFINITY;
+      bmax = fmaxf(bmax, sacc[r]);
+    }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+    const float m_new = fmaxf(m_run, bmax);
+    const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+    float psum = 0.f, pv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      pv[r] = (m_new == -INFINITY) ? 0.f : __expf(sacc[r] - m_new);
+      psum += pv[r];
+    }
+    psum += __shfl_xor(psum, 32, 64);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[b][r] *= alpha;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      bf16x8 ph, pl;
+      split8(pv + 8 * j, ph, pl);
+#pragma unroll
+      for (int b = 0; b < DB; ++b) {
+        bf16x8 vh, vl;
+        split8(vx[j][b], vh, vl);
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, ph, oacc[b], 0, 0, 0);
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, pl, oacc[b], 0, 0, 0);
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, ph, oacc[b], 0, 0, 0);
+      }
+    }
+  }
+  // merge the 4 waves through LDS: o_s[w][d][q], d = 32b + 8(r/4) + 4hh + r%4
+#pragma unroll
+  for (int b = 0; b < DB; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_s[((size_t)w * DH + 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3)) * 32 + q] = oacc[b][r];
+  if (hh == 0) { ml_s[(w * 2 + 0) * 32 + q] = m_run; ml_s[(w * 2 + 1) * 32 + q] = l_run; }
   __syncthreads();
-  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
-    {   // scores: thread = (token tl, row quarter rq)
-      const int tl = tid & 63, rq = tid >> 6;
-      const int t = t0 + tl;
-      if (t < t_end) {
-        const CT* kp = (const CT*)kv.k + kv_offset(kv, seq, t, kvh);
-        f32x4 kr[D4];
-        if constexpr (sizeof(CT) == 4) {
+  // thread = (query q2, group of DH/8 consecutive dims)
+  const int q2 = tid & 31, dg = tid >> 5;
+  constexpr int DPT = DH / 8;               // dims per thread (16 for DH = 128)
+  float mm = -INFINITY;
 #pragma unroll
-          for (int c = 0; c < D4; ++c) kr[c] = *(const f32x4*)((const float*)kp + 4 * c);
-        } else {
+  for (int ww = 0; ww < 4; ++ww) mm = fmaxf(mm, ml_s[(ww * 2) * 32 + q2]);
+  float wgt[4], L = 0.f;
 #pragma unroll
-          for (int c = 0; c < D4; c += 2) {
-            u32x4 raw = *(const u32x4*)((const bf16_t*)kp + 4 * c);
-            kr[c] = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
-                          __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
-            kr[c + 1] = f32x4{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xFFFF0000u),
-                              __builtin_bit_cast(float, raw.w << 16), __builtin_bit_cast(float, raw.w & 0xFFFF0000u)};
-          }
-        }
-        for (int r = rq; r < R; r += 4) {
-          f32x4 sd = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int c = 0; c < D4; ++c) sd += *(const f32x4*)&q_s[r][4 * c] * kr[c];
-          bool vis = t < base;
-          if (!vis) {
-            int j = t - base;
-            vis = causal_s[r] ? (j <= rel_s[r]) : (j < 64 && ((mask_s[r] >> j) & 1ull));
-          }
-          s_s[r][tl] = vis ? (sd.x + sd.y) + (sd.z + sd.w) : -INFINITY;
-        }
-      } else {
-        for (int r = rq; r < R; r += 4) s_s[r][tl] = -INFINITY;
-      }
-    }
-    __syncthreads();
-    {   // running max / sum: wave w handles rows w, w+4, ...; lane = token
-      const int lane = tid & 63, w = tid >> 6;
-      for (int r = w; r < R; r += 4) {
-        float sv = s_s[r][lane];
-        float mx = wave_max(sv);
-        float m_old = m_s[r];
-        float m_new = fmaxf(m_old, mx);
-        float p = (m_new == -INFINITY) ? 0.f : __expf(sv - m_new);
-        float al = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
-        float ps = wave_sum(p);
-        s_s[r][lane] = p;
-        if (lane == 0) { m_s[r] = m_new; l_s[r] = l_s[r] * al + ps; alpha_s[r] = al; }
-      }
-    }
-    __syncthreads();
-    {   // acc = acc*alpha + P.V : thread = (float4 column d4, row group rg)
-      const int nt = min(64, t_end - t0);
-#pragma unroll
-      for (int i = 0; i < RPT; ++i) {
-        int r = rg + i * NRG;
-        if (r < R) acc[i] *= alpha_s[r];
-      }
-      for (int tb = 0; tb < nt; tb += 8) {               // 8 V rows in flight per thread
-        f32x4 vv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int tl = min(tb + u, nt - 1);
-          const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
-          if constexpr (sizeof(CT) == 4) vv[u] = *(const f32x4*)((const float*)vp + 4 * d4);
-          else {
-            const uint2 raw = *(const uint2*)((const bf16_t*)vp + 4 * d4);
-            vv[u] = f32x4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xFFFF0000u),
-                          __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xFFFF0000u)};
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          if (tb + u < nt) {
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-              int r = rg + i * NRG;
-              if (r < R) acc[i] += s_s[r][tb + u] * vv[u];
-            }
-          }
-        }
-      }
-    }
-    __syncthreads();
+  for (int ww = 0; ww < 4; ++ww) {
+    const float mw = ml_s[(ww * 2) * 32 + q2];
+    wgt[ww] = (mw == -INFINITY) ? 0.f : __expf(mw - mm);
+    L += wgt[ww] * ml_s[(ww * 2 + 1) * 32 + q2];
   }
+  float o[DPT];
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    int r = rg + i * NRG;
-    if (r < R) {
-      float* po = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + 4 * d4;
-      coh_store(po, acc[i].x); coh_store(po + 1, acc[i].y); coh_store(po + 2, acc[i].z); coh_store(po + 3, acc[i].w);
-    }
+  for (int i = 0; i < DPT; ++i) {
+    float a = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) a += wgt[ww] * o_s[((size_t)ww * DH + dg * DPT + i) * 32 + q2];
+    o[i] = a;
   }
-  if (tid < R) {
-    size_t o = (((size_t)(r0 + tid) * H + hd) * n_splits + split) * 2;
-    coh_store(part_ml + o, m_s[tid]);
-    coh_store(part_ml + o + 1, l_s[tid]);
+  const int KSX = H * DH / 16;
+  if (n_splits == 1) {
+    if (q2 < R) {
+      const float inv = L > 0.f ? 1.0f / L : 0.f;
+#pragma unroll
+      for (int c = 0; c < DPT / 8; ++c) {
+        float x[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = o[8 * c + t] * inv;
+        xf_store8(xf_out, r0 + q2, hd * DH + dg * DPT + 8 * c, 1, KSX, nplanes, x);
+      }
+    }
+    return;
+  }
+  if (q2 < R) {
+    float* po = part_o + (((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + dg * DPT;
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) coh_store(po + i, o[i]);
+    if (dg == 0) {
+      const size_t ofs = (((size_t)(r0 + q2) * H + hd) * n_splits + split) * 2;
+      coh_store(part_ml + ofs, mm);
+      coh_store(part_ml + ofs + 1, L);
+    }
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
@@ -578,47 +647,46 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   // merge the splits of (sequence, head): thread = (row, 8-wide column chunk)
-  const int KS = H * DH / 16;
   for (int it = tid; it < R * (DH / 8); it += 256) {
     const int r = it / (DH / 8), d0 = (it % (DH / 8)) * 8;
     const float* ml = part_ml + ((size_t)(r0 + r) * H + hd) * n_splits * 2;
     float msv[16], lsv[16];
 #pragma unroll
     for (int sp = 0; sp < 16; ++sp) {                          // all (max, sum) pairs in flight at once
-      const int q = min(sp, n_splits - 1);
-      msv[sp] = coh_load(ml + 2 * q);
-      lsv[sp] = coh_load(ml + 2 * q + 1);
+      const int qq = min(sp, n_splits - 1);
+      msv[sp] = coh_load(ml + 2 * qq);
+      lsv[sp] = coh_load(ml + 2 * qq + 1);
     }
-    float mm = -INFINITY;
+    float mx = -INFINITY;
 #pragma unroll
-    for (int sp = 0; sp < 16; ++sp) if (sp < n_splits) mm = fmaxf(mm, msv[sp]);
+    for (int sp = 0; sp < 16; ++sp) if (sp < n_splits) mx = fmaxf(mx, msv[sp]);
     float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     float wv[16];
 #pragma unroll
     for (int sp = 0; sp < 16; ++sp) {
-      wv[sp] = (sp < n_splits && msv[sp] != -INFINITY) ? __expf(msv[sp] - mm) : 0.f;
+      wv[sp] = (sp < n_splits && msv[sp] != -INFINITY) ? __expf(msv[sp] - mx) : 0.f;
       den += wv[sp] * lsv[sp];
     }
     for (int sp0 = 0; sp0 < n_splits; sp0 += 4) {              // 4 splits x 8 values in flight, added in split order
       float ov[4][8];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int q = min(sp0 + u, n_splits - 1);
-        const float* o = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + q) * DH + d0;
+        const int qq = min(sp0 + u, n_splits - 1);
+        const float* op = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + qq) * DH + d0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) ov[u][t] = coh_load(o + t);
+        for (int t = 0; t < 8; ++t) ov[u][t] = coh_load(op + t);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        float wgt = 0.f;
+        float wg2 = 0.f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) if (q == sp0 + u) wgt = wv[q];
+        for (int qq = 0; qq < 16; ++qq) if (qq == sp0 + u) wg2 = wv[qq];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] += wgt * ov[u][t];
+        for (int t = 0; t < 8; ++t) x[t] += wg2 * ov[u][t];
       }
     }
     const float inv = den > 0.f ? 1.0f / den : 0.f;
     for (int t = 0; t < 8; ++t) x[t] *= inv;
-    xf_store8(xf_out, r0 + r, hd * DH + d0, 1, KS, nplanes, x);
+    xf_store8(xf_out, r0 + r, hd * DH + d0, 1, KSX, nplanes, x);
   }
 }
