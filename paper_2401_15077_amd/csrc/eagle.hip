@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <vector>
 
 static thread_local char g_err[512] = "";
@@ -654,6 +655,7 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   g.W = w.w; g.wps = w.plane_stride; g.NRB = w.NRB; g.KS = w.KS; g.Npad = w.Npad; g.N = w.N;
   g.XF = XF; g.S = p.S; g.groups = p.groups; g.lanes = p.lanes; g.kparts = p.kparts;
   g.PT = c->PT2; g.counters = c->cnt_gemm;
+  { static int dbg = -1; if (dbg < 0) { const char* e = getenv("EAGLE_DEBUG_GEMM"); dbg = e ? atoi(e) : 0; } g.dbg = dbg; }
   if (groups_out) *groups_out = p.groups;
   bool timed = c->prof_mode == 2;
   if (timed) {

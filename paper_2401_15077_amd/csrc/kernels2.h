@@ -26,19 +26,44 @@ struct RowScale {            // 1/rms of the rows that produced the GEMM input; 
   int groups;
   float inv_d, eps;
 };
+// Sum of squares of row m = sum over 16 strided classes of groups, classes added in order (one fixed order for
+// every caller, whether one thread walks it or a block shares the loads).
 __device__ inline float row_rstd(const RowScale& rs, int m) {
   if (!rs.ssq) return 1.0f;
-  float a = 0.f;
-  int g = 0;
-  for (; g + 8 <= rs.groups; g += 8) {                 // 8 loads in flight, summed in group order
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = rs.ssq[(g + i) * 32 + m];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a += v[i];
+  float tot = 0.f;
+  for (int c = 0; c < 16; ++c) {
+    float a = 0.f;
+    for (int g = c; g < rs.groups; g += 16) a += rs.ssq[g * 32 + m];
+    tot += a;
   }
-  for (; g < rs.groups; ++g) a += rs.ssq[g * 32 + m];
-  return 1.0f / sqrtf(a * rs.inv_d + rs.eps);
+  return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
+}
+// Same value for all 32 rows at once, computed by a 512-thread block: thread (m, class c) loads its class's
+// groups (at most 16, all in flight), classes are combined through LDS.  out[32], tmp[16*32] in LDS.
+__device__ inline void block_rstd(const RowScale& rs, float* out, float* tmp) {
+  const int m = threadIdx.x & 31, c = threadIdx.x >> 5;
+  if (!rs.ssq) {
+    if (threadIdx.x < 32) out[threadIdx.x] = 1.0f;
+    __syncthreads();
+    return;
+  }
+  float v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int g = c + 16 * i;
+    v[i] = g < rs.groups ? rs.ssq[g * 32 + m] : 0.f;
+  }
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a += v[i];
+  tmp[c * 32 + m] = a;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    float tot = 0.f;
+    for (int cc = 0; cc < 16; ++cc) tot += tmp[cc * 32 + threadIdx.x];
+    out[threadIdx.x] = 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
+  }
+  __syncthreads();
 }
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
@@ -56,6 +81,7 @@ struct Gemm2 {
   const float* h_in; float* h_out; const float* bias; const float* gain_next; bf16_t* xf_out; int xf_KS; float* ssq_out; int d;
   // EPI_LOGITS
   float* logits; int out_kind, V, only_last_row;
+  int dbg;                                // timing experiments only (0 in normal use): 1 = no epilogue, 2 = stop after the main loop, 4 = no main loop
 };
 
 // out[t] = sum over the K splits of PT[s][rows[t]][m], t < 8: eight coherent loads in flight per split, splits
@@ -64,24 +90,32 @@ struct Gemm2 {
 __device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) out[t] = 0.f;
-  for (int s = 0; s < S; ++s) {
-    float v[8];
+  for (int s0 = 0; s0 < S; s0 += 4) {                        // 4 splits x 8 rows in flight
+    float v[4][8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) v[t] = coh_load(PT + ((size_t)s * Npad + rows[t]) * 32 + m);
+    for (int u = 0; u < 4; ++u) {
+      const int s = min(s0 + u, S - 1);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) out[t] += v[t];
+      for (int t = 0; t < 8; ++t) v[u][t] = coh_load(PT + ((size_t)s * Npad + rows[t]) * 32 + m);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (s0 + u < S) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t] += v[u][t];
+      }
   }
 }
 
 template <int NXP>
-__device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1) {
+__device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float* rstd_s) {
   const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
   const int dh = g.kv.head_dim, half = dh >> 1, KVH = g.kv.n_kv_heads, H = g.H;
   const bool live = m < g.M;
   RowInfo ri;
   ri.valid = 0; ri.pos = 0; ri.seq = 0; ri.slot = 0;
   if (live) ri = row_info(g.pass, g.tree, g.st, m);
-  const float rs = live ? row_rstd(g.in_scale, m) : 0.f;
+  const float rs = live ? rstd_s[m] : 0.f;
   const int npairs = (n1 - n0) >> 1;
   constexpr int SL = V2_THREADS / 32;
   for (int p0 = slot; p0 < npairs; p0 += 4 * SL) {          // four pairs (eight rows) per batch
@@ -157,10 +191,10 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
 }
 
 template <int NXP>
-__device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1) {
+__device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const float* rstd_s) {
   const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
   const bool live = m < g.M;
-  const float rs = live ? row_rstd(g.in_scale, m) : 0.f;
+  const float rs = live ? rstd_s[m] : 0.f;
   const int items = ((n1 - n0) >> 5) * 2;
   for (int it = slot; it < items; it += V2_THREADS / 32) {
     const int rb = it >> 1, c2 = it & 1;
@@ -181,10 +215,10 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1) {
   }
 }
 
-__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/) {
+__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/, const float* rstd_s) {
   const int a = threadIdx.x & 31, b = threadIdx.x >> 5;        // read side: m = a, row b of 16
   const int a2 = threadIdx.x & 15, b2 = threadIdx.x >> 4;      // write side: n = a2, m = b2
-  const float rs = a < g.M ? row_rstd(g.in_scale, a) : 0.f;
+  const float rs = a < g.M ? rstd_s[a] : 0.f;
   long dst = -1;
   if (b2 < g.M) {
     RowInfo ri = row_info(g.pass, g.tree, g.st, b2);
@@ -210,12 +244,14 @@ __device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh
   }
 }
 
-template <int NWP, int NXP, int NR, int DEPTH>
-__device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, int kb, int ke, const u32x4* const* wp,
-                                          size_t wps, f32x16* acc, int lane) {
-  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+// The streaming loop of one wave: NR weight blocks over k-steps [kb, ke), DEPTH k-steps (DEPTH*NR tiles of 1 KiB)
+// in flight.  Loads are issued unconditionally (indices clamped to the last step) so that the number in flight is
+// static and the compiler waits for exactly the tile it needs.  The first DEPTH steps are requested by
+// k2_prologue BEFORE the block stages its X slice, so HBM is already busy while LDS is being filled.
+// Tile registers: pre[(dd*NR + j)*NWP + p].
+template <int NWP, int NR, int DEPTH>
+__device__ __forceinline__ void k2_prologue(int kb, int ke, const u32x4* const* wp, size_t wps, u32x4* pre) {
   if (ke <= kb) return;
-  u32x4 abuf[DEPTH][NR][NWP];
   const int klast = ke - 1;
 #pragma unroll
   for (int dd = 0; dd < DEPTH; ++dd) {
@@ -223,8 +259,16 @@ __device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, 
 #pragma unroll
     for (int j = 0; j < NR; ++j)
 #pragma unroll
-      for (int p = 0; p < NWP; ++p) abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
+      for (int p = 0; p < NWP; ++p) pre[(dd * NR + j) * NWP + p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
   }
+}
+
+template <int NWP, int NXP, int NR, int DEPTH>
+__device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, int kb, int ke, const u32x4* const* wp,
+                                          size_t wps, f32x16* acc, int lane, u32x4* pre) {
+  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+  if (ke <= kb) return;
+  const int klast = ke - 1;
   int k = kb;
   for (; k + DEPTH < ke; k += DEPTH) {
 #pragma unroll
@@ -240,13 +284,13 @@ __device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, 
 #pragma unroll
           for (int q = 0; q < NXP; ++q)
             if (p + q < PMAX)
-              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pre[(dd * NR + j) * NWP + p]),
                                                                 __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
       const int kn = min(kk + DEPTH, klast);
 #pragma unroll
       for (int j = 0; j < NR; ++j)
 #pragma unroll
-        for (int p = 0; p < NWP; ++p) abuf[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kn * 64) + p * wps);
+        for (int p = 0; p < NWP; ++p) pre[(dd * NR + j) * NWP + p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kn * 64) + p * wps);
       __builtin_amdgcn_sched_barrier(0);          // keep "use a slot, refill that slot" in program order
     }
   }
@@ -264,17 +308,22 @@ __device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, 
 #pragma unroll
           for (int q = 0; q < NXP; ++q)
             if (p + q < PMAX)
-              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, abuf[dd][j][p]),
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pre[(dd * NR + j) * NWP + p]),
                                                                 __builtin_bit_cast(bf16x8, bq[q]), acc[j], 0, 0, 0);
     }
   }
 }
 
 template <int NWP, int NXP, int RW, int NR, int DEPTH>
+__device__ __forceinline__ void k2_prologue_dispatch(int nr, int kb, int ke, const u32x4* const* wp, size_t wps, u32x4* pre) {
+  if (nr == NR) k2_prologue<NWP, NR, (DEPTH * RW) / NR>(kb, ke, wp, wps, pre);
+  else if constexpr (NR > 1) k2_prologue_dispatch<NWP, NXP, RW, NR - 1, DEPTH>(nr, kb, ke, wp, wps, pre);
+}
+template <int NWP, int NXP, int RW, int NR, int DEPTH>
 __device__ __forceinline__ void k2_stream_dispatch(int nr, const u32x4* xs, int kt, int kb, int ke, const u32x4* const* wp,
-                                                   size_t wps, f32x16* acc, int lane) {
-  if (nr == NR) k2_stream<NWP, NXP, NR, DEPTH>(xs, kt, kb, ke, wp, wps, acc, lane);
-  else if constexpr (NR > 1) k2_stream_dispatch<NWP, NXP, RW, NR - 1, DEPTH>(nr, xs, kt, kb, ke, wp, wps, acc, lane);
+                                                   size_t wps, f32x16* acc, int lane, u32x4* pre) {
+  if (nr == NR) k2_stream<NWP, NXP, NR, (DEPTH * RW) / NR>(xs, kt, kb, ke, wp, wps, acc, lane, pre);
+  else if constexpr (NR > 1) k2_stream_dispatch<NWP, NXP, RW, NR - 1, DEPTH>(nr, xs, kt, kb, ke, wp, wps, acc, lane, pre);
 }
 
 template <int NWP, int NXP, int RW, int DEPTH>
@@ -291,6 +340,18 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   const int kb = (int)((long)kb_i * kt / g.kparts), ke = (int)((long)(kb_i + 1) * kt / g.kparts);
   int nr = 0;
   for (int j = 0; j < RW; ++j) nr += (rb0 + la + j * g.lanes < rb1) ? 1 : 0;
+  nr = __builtin_amdgcn_readfirstlane(nr);
+
+  const u32x4* wp[RW];
+#pragma unroll
+  for (int j = 0; j < RW; ++j) {
+    int rb = rb0 + la + j * g.lanes;
+    if (rb >= rb1) rb = rb0;                                  // never dereferenced: only the first nr entries are used
+    wp[j] = (const u32x4*)(g.W + ((size_t)rb * g.KS + ks0) * 512) + lane;
+  }
+  // the first weight tiles are requested before anything else (a wave with fewer row blocks keeps more k-steps in flight)
+  u32x4 pre[DEPTH * RW * NWP];
+  if (!(g.dbg & 4)) k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
 
   // stage this work-group's K slice of X: per plane a contiguous run of kt tiles (8 loads in flight per thread)
   for (int p = 0; p < NXP; ++p) {
@@ -313,15 +374,9 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   for (int j = 0; j < RW; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  const u32x4* wp[RW];
-#pragma unroll
-  for (int j = 0; j < RW; ++j) {
-    int rb = rb0 + la + j * g.lanes;
-    if (rb >= rb1) rb = rb0;                                  // never dereferenced: only the first nr entries are used
-    wp[j] = (const u32x4*)(g.W + ((size_t)rb * g.KS + ks0) * 512) + lane;
-  }
   __syncthreads();
-  k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane);
+  if (!(g.dbg & 4)) k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane, pre);
+  if (g.dbg & 2) { if (acc[0][0] == 123.456f) g.PT[0] = 1.f; return; }
   // waves that split K inside the work-group: sum through LDS in k-part order
   if (g.kparts > 1) {
     __syncthreads();                                          // the X slice is no longer needed
@@ -364,15 +419,17 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     if (s_last) __hip_atomic_store(g.counters + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!s_last || (g.dbg & 1)) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
   if (n1 <= n0) return;
+  __shared__ float rstd_s[32];
+  if (g.epi != EPI_RESID) block_rstd(g.in_scale, rstd_s, sh_small);
   switch (g.epi) {
-    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1); break;
+    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1, rstd_s); break;
     case EPI_RESID: epilogue_resid<NXP>(g, grp, n0, n1, sh_small); break;
-    case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1); break;
-    default: epilogue_logits(g, n0, n1, sh_small); break;
+    case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
+    default: epilogue_logits(g, n0, n1, sh_small, rstd_s); break;
   }
 }
 
