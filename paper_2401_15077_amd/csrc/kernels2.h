@@ -647,9 +647,8 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     for (int r = 0; r < 16; ++r) o_s[((size_t)w * DH + 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3)) * 32 + q] = oacc[b][r];
   if (hh == 0) { ml_s[(w * 2 + 0) * 32 + q] = m_run; ml_s[(w * 2 + 1) * 32 + q] = l_run; }
   __syncthreads();
-  // thread = (query q2, group of DH/8 consecutive dims)
-  const int q2 = tid & 31, dg = tid >> 5;
-  constexpr int DPT = DH / 8;               // dims per thread (16 for DH = 128)
+  // thread = (query q2, 8-wide chunks c = tid/32, tid/32 + 8, ... of the head dimension)
+  const int q2 = tid & 31;
   float mm = -INFINITY;
 #pragma unroll
   for (int ww = 0; ww < 4; ++ww) mm = fmaxf(mm, ml_s[(ww * 2) * 32 + q2]);
@@ -660,37 +659,33 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     wgt[ww] = (mw == -INFINITY) ? 0.f : __expf(mw - mm);
     L += wgt[ww] * ml_s[(ww * 2 + 1) * 32 + q2];
   }
-  float o[DPT];
-#pragma unroll
-  for (int i = 0; i < DPT; ++i) {
-    float a = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) a += wgt[ww] * o_s[((size_t)ww * DH + dg * DPT + i) * 32 + q2];
-    o[i] = a;
-  }
   const int KSX = H * DH / 16;
-  if (n_splits == 1) {
-    if (q2 < R) {
-      const float inv = L > 0.f ? 1.0f / L : 0.f;
+  const float inv = L > 0.f ? 1.0f / L : 0.f;
+  for (int c = tid >> 5; c < DH / 8; c += 8) {
+    float o[8];
 #pragma unroll
-      for (int c = 0; c < DPT / 8; ++c) {
-        float x[8];
+    for (int i = 0; i < 8; ++i) {
+      float a = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = o[8 * c + t] * inv;
-        xf_store8(xf_out, r0 + q2, hd * DH + dg * DPT + 8 * c, 1, KSX, nplanes, x);
-      }
+      for (int ww = 0; ww < 4; ++ww) a += wgt[ww] * o_s[((size_t)ww * DH + 8 * c + i) * 32 + q2];
+      o[i] = a;
     }
-    return;
+    if (q2 >= R) continue;
+    if (n_splits == 1) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) o[t] *= inv;
+      xf_store8(xf_out, r0 + q2, hd * DH + 8 * c, 1, KSX, nplanes, o);
+    } else {
+      float* po = part_o + (((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + 8 * c;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) coh_store(po + i, o[i]);
+    }
   }
-  if (q2 < R) {
-    float* po = part_o + (((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + dg * DPT;
-#pragma unroll
-    for (int i = 0; i < DPT; ++i) coh_store(po + i, o[i]);
-    if (dg == 0) {
-      const size_t ofs = (((size_t)(r0 + q2) * H + hd) * n_splits + split) * 2;
-      coh_store(part_ml + ofs, mm);
-      coh_store(part_ml + ofs + 1, L);
-    }
+  if (n_splits == 1) return;
+  if (q2 < R && tid < 32) {
+    const size_t ofs = (((size_t)(r0 + q2) * H + hd) * n_splits + split) * 2;
+    coh_store(part_ml + ofs, mm);
+    coh_store(part_ml + ofs + 1, L);
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();

@@ -112,3 +112,35 @@ def test_llama7b_twin_bf16_lockstep():
     st, toks, future = run_twin("llama2-7b", "T26", seed=2, n_layers=2, prompt_len=96, n_new=48, alpha=0.7773)
     assert toks[:96 + 48] == future[:96 + 48]          # speculative == the GPU's vanilla decoding
     assert st.tau > 2.0
+
+
+def test_tiny_stochastic_lockstep():
+    """Temperature 1: children drawn without replacement (Gumbel top-k), Alg. 1 at every node, counter-based draws.
+    Every accept test / draw whose oracle margin is not marginal must agree bit for bit."""
+    s, eng, orc = make_pair("tiny", "T15", seed=4, temperature=1.0, rng_seed=2024)
+    prompt = synth.prompt(4, 24, s.vocab)
+    check_prefill(eng, orc, prompt, TOL["fp32"], margin_thr=1e-4)
+    st = Stats()
+    while len(orc.x) < len(prompt) + 48:
+        lockstep_step(eng, orc, st, TOL["fp32"], margin_thr=1e-3, stoch_margin=1e-3)
+    print(f"stochastic: steps={st.steps} tau={st.tau:.2f} max|dL|={st.max_logit_err:.2e} excused tree/accept="
+          f"{st.excused_tree_slots}/{st.excused_accepts} lens={st.lens}", flush=True)
+    assert st.excused_accepts <= 1 and st.excused_tree_slots <= 2
+    assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x
+    # reproducible: the same seed gives the same tokens
+    eng.reset()
+    eng.prefill(0, prompt)
+    n = len(orc.x) - len(prompt)
+    out = [int(eng.get_buffer(pkg.BUF_TOKENS)[-1])]
+    while len(out) < n:
+        toks, lens, _ = eng.step()
+        out += [int(t) for t in toks[0][:lens[0]]]
+    assert out[:n] == orc.x[len(prompt):len(prompt) + n]
+    eng.close()
+
+
+def test_gqa_twin_bf16_lockstep():
+    """LLaMA2-70B widths are too large for a unit test; a grouped-query model (8 query heads on 2 KV heads) with the
+    bf16 path and T10 tree exercises the head -> KV-head mapping, and the tiny T26 run above the 26-node tree."""
+    st, toks, future = run_twin("mini-gqa", "T10", seed=5, n_layers=2, prompt_len=40, n_new=40, alpha=0.6, max_seq=256)
+    assert toks[:80] == future[:80]
