@@ -80,7 +80,8 @@ struct eagle_ctx {
   size_t pt_floats;
   // fast path (passes of <= 32 rows)
   float *h2, *PT2, *ssq1, *ssq2; int *cnt_gemm, *cnt_attn; size_t pt2_floats;
-  bf16_t *xf2_d, *xf2_2d, *xf2_att, *xf2_ffn;
+  bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
+  float *moe_w, *xn; int* expert_used;    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
   int n_cu = 256;
   // host mirror
@@ -286,6 +287,10 @@ static size_t layout(eagle_ctx* c) {
   // fast path buffers
   c->h2 = a.take<float>((size_t)32 * d);
   c->xf2_d = a.take<bf16_t>((size_t)c->NXP * 32 * d);
+  c->xf2_dB = a.take<bf16_t>(g.n_experts > 0 ? (size_t)c->NXP * 32 * d : 8);
+  c->moe_w = a.take<float>((size_t)std::max(1, g.n_experts) * 128);
+  c->expert_used = a.take<int>(std::max(1, g.n_experts));
+  c->xn = a.take<float>(g.n_experts > 0 ? (size_t)Mm * d : 8);
   c->xf2_2d = a.take<bf16_t>((size_t)c->NXP * 32 * 2 * d);
   c->xf2_att = a.take<bf16_t>((size_t)c->NXP * 32 * H * dh);
   c->xf2_ffn = a.take<bf16_t>((size_t)c->NXP * 32 * F);
@@ -539,8 +544,8 @@ static KVCache kv_for(eagle_ctx* c, int li) {
 }
 
 static int resnorm(eagle_ctx* c, int M, int MT, const float* h_in, const float* PT, int S, int Npad, const float* bias,
-                   const float* gain, bf16_t* XF, float* xout) {
-  k_resnorm<<<M, 256, 0, c->stream>>>(h_in, PT, S, Npad, MT * 32, bias, c->h, gain, c->cfg.rms_eps, XF, MT, c->NXP, xout, c->cfg.d_model);
+                   const float* gain, bf16_t* XF, float* xout, const float* row_w = nullptr) {
+  k_resnorm<<<M, 256, 0, c->stream>>>(h_in, PT, S, Npad, MT * 32, bias, c->h, gain, c->cfg.rms_eps, XF, MT, c->NXP, xout, c->cfg.d_model, row_w);
   LAUNCH_CHECK();
   return EAGLE_OK;
 }
@@ -574,8 +579,27 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     LAUNCH_CHECK();
   }
   if ((rc = gemm(c, w.o, c->xf_att, MT, &S))) return rc;
-  if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.o.Npad, nullptr, w.mlp_norm, c->xf_d, nullptr))) return rc;
-  if (w.moe) return fail(EAGLE_EINVAL, "MoE layers are not implemented yet");
+  if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.o.Npad, nullptr, w.mlp_norm, c->xf_d, w.moe ? c->xn : nullptr))) return rc;
+  if (w.moe) {
+    // top-k routed experts: every expert runs over all rows of the pass (the cost is the weight stream, not the
+    // rows); a row's result is scaled by its routing weight, which is 0 for experts it did not select
+    const int E = g.n_experts;
+    k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->expert_used, 0u, (size_t)E);
+    LAUNCH_CHECK();
+    k_router<<<M, 256, 0, c->stream>>>(c->xn, nullptr, nullptr, 0, 0.f, 0.f, nullptr, w.router, E, g.experts_per_tok, g.d_model, M, c->moe_w, 128, c->expert_used);
+    LAUNCH_CHECK();
+    for (int e = 0; e < E; ++e) {
+      if ((rc = gemm(c, w.e_gu[e], c->xf_d, MT, &S))) return rc;
+      dim3 grid((F / 8 + 255) / 256, M);
+      k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.e_gu[e].Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
+      LAUNCH_CHECK();
+      if ((rc = gemm(c, w.e_dn[e], c->xf_ffn, MT, &S))) return rc;
+      const bool last = e + 1 == E;     // only the last expert's pass produces the normalised output
+      if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.e_dn[e].Npad, nullptr, last ? next_gain : nullptr, last ? c->xf_d : nullptr,
+                        last ? xout : nullptr, c->moe_w + (size_t)e * 128))) return rc;
+    }
+    return EAGLE_OK;
+  }
   if ((rc = gemm(c, w.gu, c->xf_d, MT, &S))) return rc;
   {
     dim3 grid((F / 8 + 255) / 256, M);
@@ -704,7 +728,6 @@ static RowScale scale_of(eagle_ctx* c, const float* ssq, int groups) {
 static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, int n_new, const float* next_gain) {
   const eagle_config& cf = c->cfg;
   LayerW& w = c->layers[li];
-  if (w.moe) return fail(EAGLE_EINVAL, "MoE layers are not implemented yet");
   const int H = cf.n_heads, dh = cf.head_dim, d = cf.d_model, F = cf.d_ffn;
   int rc;
   Gemm2 g = gemm2_base(c, pass, M);
@@ -733,6 +756,27 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   g = gemm2_base(c, pass, M);
   g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = w.mlp_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq1;
   if ((rc = gemm2(c, w.o, c->xf2_att, g, &c->ssq1_groups))) return rc;
+  if (w.moe) {
+    // routed experts (see the general path): experts no row selected are skipped on the device (skip_flag)
+    const int E = cf.n_experts;
+    k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->expert_used, 0u, (size_t)E);
+    LAUNCH_CHECK();
+    k_router<<<M, 256, 0, c->stream>>>(nullptr, c->h2, c->ssq1, c->ssq1_groups, 1.0f / (float)d, cf.rms_eps, w.mlp_norm, w.router, E,
+                                       cf.experts_per_tok, d, M, c->moe_w, 128, c->expert_used);
+    LAUNCH_CHECK();
+    for (int e = 0; e < E; ++e) {
+      g = gemm2_base(c, pass, M);
+      g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
+      g.skip_flag = c->expert_used + e;
+      if ((rc = gemm2(c, w.e_gu[e], c->xf2_d, g, nullptr))) return rc;
+      g = gemm2_base(c, pass, M);
+      g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = next_gain; g.xf_out = c->xf2_dB; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
+      g.row_w = c->moe_w + (size_t)e * 128; g.skip_flag = c->expert_used + e;
+      if ((rc = gemm2(c, w.e_dn[e], c->xf2_ffn, g, &c->ssq2_groups))) return rc;
+    }
+    std::swap(c->xf2_d, c->xf2_dB);     // the experts all read the old xf2_d; the new one was built beside it
+    return EAGLE_OK;
+  }
   g = gemm2_base(c, pass, M);
   g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
   if ((rc = gemm2(c, w.gu, c->xf2_d, g, nullptr))) return rc;

@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void k_fc_input(Pass pass, const TreeDev* tree
 // x goes out in XF layout (GEMM input) and, optionally, as fp32 rows (features).  One block per row.
 __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float* __restrict__ PT, int S, int Npad, int Mpad,
                                                  const float* bias, float* h_out, const float* gain, float eps,
-                                                 bf16_t* XF, int MT, int nplanes, float* xout, int d) {
+                                                 bf16_t* XF, int MT, int nplanes, float* xout, int d, const float* row_w) {
   __shared__ float sh[16];
   int r = blockIdx.x;
   float ss = 0.f;
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float*
       if (PT) {
         float a = 0.f;
         for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + k) * Mpad + r];
-        v += a;
+        v += row_w ? row_w[r] * a : a;            // MoE: this expert's routing weight for the row (0 = not routed here)
       }
       if (bias) v += bias[k];
       h_out[(size_t)r * d + k] = v;
@@ -887,6 +887,58 @@ __global__ __launch_bounds__(256) void k_compact(const TreeDev* tree, SeqState s
       if (pth[i] == i) continue;
       u32x4 val = *(const u32x4*)(cache + kv_offset(kv, seq, base + pth[i], kvh) + off);
       *(u32x4*)(cache + kv_offset(kv, seq, base + i, kvh) + off) = val;
+    }
+  }
+}
+
+// ============================================================================ MoE router
+// Row r: x = the normalised MLP input (given, or h * rstd * gain), router logits in fp32, top-k experts (equal
+// logits -> lower expert id), softmax over the selected logits.  Writes the dense routing weights
+// moe_w[e][row_stride] (0 where the row does not use expert e) and expert_used[e].  Block = one row.
+__global__ __launch_bounds__(256) void k_router(const float* xnorm, const float* h, const float* ssq, int ssq_groups, float inv_d,
+                                                float eps, const float* gain, const float* __restrict__ router, int E, int topk,
+                                                int d, int M, float* moe_w, int row_stride, int* expert_used) {
+  __shared__ float sh[16];
+  __shared__ float lg[64];
+  const int r = blockIdx.x;
+  float rstd = 1.f;
+  if (!xnorm) {
+    float tot = 0.f;
+    for (int c = 0; c < 16; ++c) {
+      float a = 0.f;
+      for (int g = c; g < ssq_groups; g += 16) a += ssq[g * 32 + r];
+      tot += a;
+    }
+    rstd = 1.0f / sqrtf(tot * inv_d + eps);
+  }
+  for (int e = 0; e < E; ++e) {
+    float a = 0.f;
+    for (int k = threadIdx.x; k < d; k += blockDim.x) {
+      const float x = xnorm ? xnorm[(size_t)r * d + k] : h[(size_t)r * d + k] * rstd * gain[k];
+      a += x * router[(size_t)e * d + k];
+    }
+    a = block_sum(a, sh);
+    if (threadIdx.x == 0) lg[e] = a;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int sel[4];
+    float sv[4];
+    for (int j = 0; j < topk; ++j) {
+      float bv = -INFINITY; int bi = 0x7fffffff;
+      for (int e = 0; e < E; ++e) {
+        bool taken = false;
+        for (int q = 0; q < j; ++q) taken |= (sel[q] == e);
+        if (!taken) better(bv, bi, lg[e], e);
+      }
+      sel[j] = bi; sv[j] = bv;
+    }
+    float mx = sv[0], den = 0.f, p[4];
+    for (int j = 0; j < topk; ++j) { p[j] = expf(sv[j] - mx); den += p[j]; }
+    for (int e = 0; e < E; ++e) moe_w[(size_t)e * row_stride + r] = 0.f;
+    for (int j = 0; j < topk; ++j) {
+      moe_w[(size_t)sel[j] * row_stride + r] = p[j] / den;
+      if (r < M) atomicOr(expert_used + sel[j], 1);
     }
   }
 }

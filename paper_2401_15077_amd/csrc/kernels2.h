@@ -81,6 +81,8 @@ struct Gemm2 {
   const float* h_in; float* h_out; const float* bias; const float* gain_next; bf16_t* xf_out; int xf_KS; float* ssq_out; int d;
   // EPI_LOGITS
   float* logits; int out_kind, V, only_last_row;
+  const float* row_w;                     // MoE: per-row routing weight applied to this GEMM's result (nullptr = 1)
+  const int* skip_flag;                   // MoE: the whole launch is a no-op when *skip_flag == 0 (no row uses the expert)
   int dbg;                                // timing experiments only (0 in normal use): 1 = no epilogue, 2 = stop after the main loop, 4 = no main loop
 };
 
@@ -170,7 +172,7 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
     for (int t = 0; t < 8; ++t) {
       float v = 0.f;
       if (n + t < n1) {
-        v = pv[t];
+        v = g.row_w ? g.row_w[m] * pv[t] : pv[t];
         if (g.bias) v += g.bias[n + t];
         if (g.h_in && live) v += g.h_in[(size_t)m * g.d + n + t];
         if (live) g.h_out[(size_t)m * g.d + n + t] = v;
@@ -331,6 +333,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sh_small[16 * 33];
   __shared__ int s_last;
+  if (g.skip_flag && *g.skip_flag == 0) return;               // uniform over the whole grid
   u32x4* xs = (u32x4*)smem;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int s = blockIdx.x % g.S, grp = blockIdx.x / g.S;

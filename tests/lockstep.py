@@ -42,7 +42,23 @@ def check_prefill(eng, orc, prompt, tol, margin_thr=2e-2, seq=0):
 
 
 def lockstep_step(eng, orc, st: Stats, tol, margin_thr=2e-2, seq=0, stoch_margin=1e-3):
-    toks = eng.draft_tree()[seq]
+    return lockstep_step_batch(eng, [orc], [st], tol, margin_thr, stoch_margin)[0]
+
+
+def lockstep_step_batch(eng, orcs, sts, tol, margin_thr=2e-2, stoch_margin=1e-3):
+    """One step of every active slot; slot i is checked against orcs[i]."""
+    all_toks = eng.draft_tree()
+    for seq, (orc, st) in enumerate(zip(orcs, sts)):
+        _check_draft(eng, orc, st, all_toks[seq], tol, margin_thr, seq)
+    eng.verify()
+    for seq, (orc, st) in enumerate(zip(orcs, sts)):
+        _check_verify(eng, orc, st, tol, seq)
+    out, lens, path = eng.accept()
+    return [_check_accept(orc, st, out[seq], int(lens[seq]), path[seq], margin_thr, stoch_margin)
+            for seq, (orc, st) in enumerate(zip(orcs, sts))]
+
+
+def _check_draft(eng, orc, st, toks, tol, margin_thr, seq):
     d = orc.draft_tree(forced_tokens=toks)
     for (v, r, t_o, t_g, gap) in d["mismatches"]:
         assert gap < margin_thr, f"tree slot (node {v}, rank {r}): oracle {t_o} vs GPU {t_g}, score gap {gap}"
@@ -54,15 +70,18 @@ def lockstep_step(eng, orc, st: Stats, tol, margin_thr=2e-2, seq=0, stoch_margin
         st.max_draft_feat_err = max(st.max_draft_feat_err, float(np.abs(df[v] - orc.node_f[v]).max()))
     assert st.max_draft_logit_err <= tol and st.max_draft_feat_err <= tol, \
         f"draft logits/features differ by {st.max_draft_logit_err} / {st.max_draft_feat_err}"
-    eng.verify()
+
+
+def _check_verify(eng, orc, st, tol, seq):
     F, L = orc.verify()
     st.max_logit_err = max(st.max_logit_err, float(np.abs(eng.get_buffer(pkg.BUF_LOGITS, seq) - L).max()))
     st.max_feat_err = max(st.max_feat_err, float(np.abs(eng.get_buffer(pkg.BUF_FEATURES, seq) - F).max()))
     assert st.max_logit_err <= tol and st.max_feat_err <= tol, \
         f"verify logits/features differ by {st.max_logit_err} / {st.max_feat_err}"
-    out, lens, path = eng.accept()
-    n = int(lens[seq])
-    g_path, g_out = [int(x) for x in path[seq][:n]], [int(x) for x in out[seq][:n]]
+
+
+def _check_accept(orc, st, out, n, path, margin_thr, stoch_margin):
+    g_path, g_out = [int(x) for x in path[:n]], [int(x) for x in out[:n]]
     r = orc.accept()
     assert 1 <= n <= orc.tree.D + 1
     assert g_path[0] == 0 and all(orc.tree.parent[g_path[i + 1]] == g_path[i] for i in range(n - 1))

@@ -4,7 +4,7 @@ import pytest
 
 import paper_2401_15077_amd as pkg
 import synth
-from lockstep import Stats, check_prefill, lockstep_step
+from lockstep import Stats, check_prefill, lockstep_step, lockstep_step_batch
 from oracle.eagle_oracle import Oracle, u24, PURPOSE_HINT
 
 pytestmark = pytest.mark.gpu
@@ -81,8 +81,8 @@ def test_tiny_hint_knob_accept_lengths_and_compaction():
     eng.close()
 
 
-def run_twin(shape_name, tree, seed, n_layers, prompt_len, n_new, alpha, max_seq=512):
-    s, eng, orc = make_pair(shape_name, tree, seed=seed, max_seq=max_seq, dtype=np.float32, n_layers=n_layers)
+def run_twin(shape_name, tree, seed, n_layers, prompt_len, n_new, alpha, max_seq=512, dtype=np.float32):
+    s, eng, orc = make_pair(shape_name, tree, seed=seed, max_seq=max_seq, dtype=dtype, n_layers=n_layers)
     prompt = synth.prompt(seed, prompt_len, s.vocab)
     print(f"{s.name}: prefill", flush=True)
     # the knob follows the GPU's own vanilla continuation (as the benchmark does)
@@ -144,3 +144,33 @@ def test_gqa_twin_bf16_lockstep():
     bf16 path and T10 tree exercises the head -> KV-head mapping, and the tiny T26 run above the 26-node tree."""
     st, toks, future = run_twin("mini-gqa", "T10", seed=5, n_layers=2, prompt_len=40, n_new=40, alpha=0.6, max_seq=256)
     assert toks[:80] == future[:80]
+
+
+def test_moe_twin_bf16_lockstep():
+    """Top-2 routed experts in the target AND in the head's layer (the Mixtral-shaped configuration in small):
+    4 experts, grouped-query attention, bf16 weights.  The oracle runs in fp64 so that router near-ties are not an issue."""
+    st, toks, future = run_twin("mini-moe", "T15", seed=6, n_layers=2, prompt_len=40, n_new=40, alpha=0.6, max_seq=256,
+                                dtype=np.float64)
+    assert toks[:80] == future[:80]
+
+
+def test_batch4_lockstep():
+    """Four independent sequences (different prompts) advance together: rows of all slots share the GEMMs
+    (verify has 4 x 15 = 60 rows and takes the general path, the head's tree levels take the fast path)."""
+    s = synth.SHAPES["tiny"]
+    par, rk = synth.TREES["T15"]
+    eng = pkg.Eagle(s, par, rk, max_batch=4, max_seq=160)
+    eng.load_weights(synth.iter_weights(s, 1, synth.device_fmt(s)))
+    W = synth.make_weights(s, 1, synth.oracle_fmt(s))
+    orcs, sts = [], []
+    for b in range(4):
+        orc = Oracle(s, W, par, rk, max_seq=160, seq_id=b)
+        prompt = synth.prompt(1, 12 + 5 * b, s.vocab, stream=b)
+        check_prefill(eng, orc, prompt, TOL["fp32"], seq=b)
+        orcs.append(orc); sts.append(Stats())
+    for _ in range(12):
+        lockstep_step_batch(eng, orcs, sts, TOL["fp32"])
+    for b in range(4):
+        assert list(eng.get_buffer(pkg.BUF_TOKENS, b)) == orcs[b].x
+        assert sts[b].excused_accepts == 0 and sts[b].max_logit_err < 1e-4
+    eng.close()
