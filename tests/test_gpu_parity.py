@@ -174,3 +174,24 @@ def test_batch4_lockstep():
         assert list(eng.get_buffer(pkg.BUF_TOKENS, b)) == orcs[b].x
         assert sts[b].excused_accepts == 0 and sts[b].max_logit_err < 1e-4
     eng.close()
+
+
+def test_moe_stochastic_lockstep():
+    """The Mixtral-shaped configuration's mode in small: MoE target and head, temperature 1, seeded draws."""
+    s, eng, orc = make_pair("mini-moe", "T15", seed=8, temperature=1.0, rng_seed=77, n_layers=2, dtype=np.float64)
+    prompt = synth.prompt(8, 24, s.vocab)
+    check_prefill(eng, orc, prompt, TOL["bf16"], margin_thr=1e-3)
+    st = Stats()
+    for _ in range(10):
+        lockstep_step(eng, orc, st, TOL["bf16"], margin_thr=1e-3, stoch_margin=1e-3)
+    print(f"moe stochastic: steps={st.steps} tau={st.tau:.2f} max|dL|={st.max_logit_err:.2e} excused={st.excused_tree_slots}/{st.excused_accepts}", flush=True)
+    assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x and st.excused_accepts <= 1
+    eng.close()
+
+
+def test_llama7b_full_depth_lockstep():
+    """The benchmark's own configuration (LLaMA2-7B shape, all 32 layers, bf16, T26, knob) checked against the fp32
+    oracle for a few steps after a short prompt (the oracle's 27 GB of fp32 weights and its prefill bound the size)."""
+    st, toks, future = run_twin("llama2-7b", "T26", seed=2, n_layers=32, prompt_len=48, n_new=12, alpha=0.7773, max_seq=256)
+    assert toks[:60] == future[:60]
+    assert st.max_logit_err < 2e-2 and st.max_feat_err < 2e-2
