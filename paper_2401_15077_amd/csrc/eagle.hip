@@ -117,22 +117,22 @@ static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
   int groups = std::max(1, std::min(NRB, n_cu / S));
   // few row blocks: split K further (slices of at least 4 k-steps) until the grid fills the chip
   while (groups * S * 2 <= n_cu && (KS + 2 * S - 1) / (2 * S) >= 4) S *= 2;
+  // many row blocks (wide matrices with a long K): more work-groups than CUs rather than more than 3 row blocks per wave
+  const int r_cap = 24;
+  if ((NRB + groups - 1) / groups > r_cap) groups = (NRB + r_cap - 1) / r_cap;
   const int R = (NRB + groups - 1) / groups, kt = (KS + S - 1) / S;
-  const int depth_limit = NWP == 1 ? 6 : 3;                    // row blocks a wave may own (accumulator registers)
   long best = -1; int bl = 8, bk = 1;
   const int cand[4][2] = {{8, 1}, {4, 2}, {2, 4}, {1, 8}};
   for (auto& cd : cand) {
     int rw = (R + cd[0] - 1) / cd[0];
-    if (rw > depth_limit) continue;
-    int rwt = rw <= 1 ? 1 : rw <= 2 ? 2 : rw <= 3 ? 3 : 6;
-    if ((size_t)cd[0] * (cd[1] - 1) * rwt * 4 > (size_t)x_cap_kb) continue;
+    if (rw > 3) continue;
+    if ((size_t)cd[0] * (cd[1] - 1) * rw * 4 > (size_t)x_cap_kb) continue;
     long cost = (long)rw * ((kt + cd[1] - 1) / cd[1]);
     if (best < 0 || cost < best) { best = cost; bl = cd[0]; bk = cd[1]; }
   }
-  if (best < 0) { bl = 8; bk = 1; }                            // caller checks RW against the limit
   p.S = S; p.groups = groups; p.lanes = bl; p.kparts = bk;
   int rw = (R + bl - 1) / bl;
-  p.RW = rw <= 1 ? 1 : rw <= 2 ? 2 : rw <= 3 ? 3 : 6;
+  p.RW = rw <= 1 ? 1 : rw <= 2 ? 2 : 3;
   p.kt_max = kt;
   size_t xs = (size_t)NXP * kt * 1024, red = (size_t)bl * (bk - 1) * p.RW * 4096;
   p.lds = std::max(xs, red);
@@ -675,11 +675,12 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   const int R = (w.NRB + p.groups - 1) / p.groups;
   if ((R + p.lanes - 1) / p.lanes > p.RW) return fail(EAGLE_EINVAL, "internal: %d row blocks per wave exceed the kernel's %d", (R + p.lanes - 1) / p.lanes, p.RW);
   if ((size_t)p.S * w.Npad * 32 > c->pt2_floats) return fail(EAGLE_EINVAL, "internal: fast-path partial buffer too small");
-  if (p.groups > 256 || p.lds > 144 * 1024 || p.lanes * p.kparts != 8) return fail(EAGLE_EINVAL, "internal: bad work split");
+  if (p.groups > 1024 || p.lds > 144 * 1024 || p.lanes * p.kparts != 8) return fail(EAGLE_EINVAL, "internal: bad work split");
   g.W = w.w; g.wps = w.plane_stride; g.NRB = w.NRB; g.KS = w.KS; g.Npad = w.Npad; g.N = w.N;
   g.XF = XF; g.S = p.S; g.groups = p.groups; g.lanes = p.lanes; g.kparts = p.kparts;
   g.PT = c->PT2; g.counters = c->cnt_gemm;
   { static int dbg = -1; if (dbg < 0) { const char* e = getenv("EAGLE_DEBUG_GEMM"); dbg = e ? atoi(e) : 0; } g.dbg = dbg; }
+  if (g.ssq_out && p.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
   if (groups_out) *groups_out = p.groups;
   bool timed = c->prof_mode == 2;
   if (timed) {
@@ -698,8 +699,7 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
     switch (p.RW) {
       case 1: e = launch_k2<1, 2, 1, 16>(g, p.lds, c->stream); break;
       case 2: e = launch_k2<1, 2, 2, 8>(g, p.lds, c->stream); break;
-      case 3: e = launch_k2<1, 2, 3, 5>(g, p.lds, c->stream); break;
-      default: e = launch_k2<1, 2, 6, 3>(g, p.lds, c->stream); break;
+      default: e = launch_k2<1, 2, 3, 5>(g, p.lds, c->stream); break;
     }
   }
   if (e != hipSuccess) return fail(EAGLE_EHIP, "fused gemm launch failed: %s", hipGetErrorString(e));

@@ -66,6 +66,37 @@ __device__ inline void block_rstd(const RowScale& rs, float* out, float* tmp) {
   __syncthreads();
 }
 
+// the per-thread class partial of block_rstd, loaded early
+__device__ inline float rstd_class_partial(const RowScale& rs) {
+  if (!rs.ssq) return 0.f;
+  const int m = threadIdx.x & 31, c = threadIdx.x >> 5;
+  float v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int g = c + 16 * i;
+    v[i] = g < rs.groups ? rs.ssq[g * 32 + m] : 0.f;
+  }
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a += v[i];
+  return a;
+}
+__device__ inline void block_rstd_finish(const RowScale& rs, float part, float* out, float* tmp) {
+  if (!rs.ssq) {
+    if (threadIdx.x < 32) out[threadIdx.x] = 1.0f;
+    __syncthreads();
+    return;
+  }
+  tmp[(threadIdx.x >> 5) * 32 + (threadIdx.x & 31)] = part;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    float tot = 0.f;
+    for (int cc = 0; cc < 16; ++cc) tot += tmp[cc * 32 + threadIdx.x];
+    out[threadIdx.x] = 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
+  }
+  __syncthreads();
+}
+
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
 struct Gemm2 {
@@ -89,43 +120,53 @@ struct Gemm2 {
 // out[t] = sum over the K splits of PT[s][rows[t]][m], t < 8: eight coherent loads in flight per split, splits
 // added in order (the loads are agent-scope atomics, which the compiler will not hoist above one another's uses
 // unless they are issued together like this).
-__device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
+template <int B>
+__device__ inline void pt_sum8_b(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
+  for (int s0 = 0; s0 < S; s0 += B) {                        // B splits x 8 rows in flight
+    float v[B][8];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) out[t] = 0.f;
-  for (int s0 = 0; s0 < S; s0 += 4) {                        // 4 splits x 8 rows in flight
-    float v[4][8];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < B; ++u) {
       const int s = min(s0 + u, S - 1);
 #pragma unroll
       for (int t = 0; t < 8; ++t) v[u][t] = coh_load(PT + ((size_t)s * Npad + rows[t]) * 32 + m);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < B; ++u)
       if (s0 + u < S) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) out[t] += v[u][t];
       }
   }
 }
+__device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) out[t] = 0.f;
+  if (S <= 4) pt_sum8_b<4>(PT, S, Npad, rows, m, out);
+  else pt_sum8_b<16>(PT, S, Npad, rows, m, out);
+}
+
+// what a thread needs about "its" row in the epilogue, fetched before the streaming loop so that the loads are
+// long finished when the last work-group gets there
+struct RowPre { int valid, seq, pos, slot; long dst; float ssq_part; };
 
 template <int NXP>
-__device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float* rstd_s) {
+__device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float* rstd_s, const RowPre& rp) {
   const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
   const int dh = g.kv.head_dim, half = dh >> 1, KVH = g.kv.n_kv_heads, H = g.H;
   const bool live = m < g.M;
-  RowInfo ri;
-  ri.valid = 0; ri.pos = 0; ri.seq = 0; ri.slot = 0;
-  if (live) ri = row_info(g.pass, g.tree, g.st, m);
   const float rs = live ? rstd_s[m] : 0.f;
   const int npairs = (n1 - n0) >> 1;
   constexpr int SL = V2_THREADS / 32;
   for (int p0 = slot; p0 < npairs; p0 += 4 * SL) {          // four pairs (eight rows) per batch
     int rows[8];
+    float cs[4], sn[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int p = min(p0 + u * SL, npairs - 1);
       rows[2 * u] = n0 + 2 * p; rows[2 * u + 1] = n0 + 2 * p + 1;
+      const int i = (rows[2 * u] % dh) >> 1;                 // rotation angle index (unused for v heads)
+      cs[u] = g.rope_cos[(size_t)rp.pos * half + i];
+      sn[u] = g.rope_sin[(size_t)rp.pos * half + i];
     }
     float val[8];
     pt_sum8(g.PT, g.S, g.Npad, rows, m, val);
@@ -137,16 +178,15 @@ __device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float*
       int d1, d2;
       if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
         const int i = pr >> 1;
-        const float c = g.rope_cos[(size_t)ri.pos * half + i], sn = g.rope_sin[(size_t)ri.pos * half + i];
-        const float a2 = a * c - b * sn, b2 = b * c + a * sn;
+        const float a2 = a * cs[u] - b * sn[u], b2 = b * cs[u] + a * sn[u];
         a = a2; b = b2; d1 = i; d2 = i + half;
       } else { d1 = pr; d2 = pr + 1; }
       if (hd < H) {
         float* q = g.Q + ((size_t)m * H + hd) * dh;
         q[d1] = a; q[d2] = b;
-      } else if (ri.valid) {
+      } else if (rp.valid) {
         const int kvh = (hd - H) % KVH;
-        const size_t off = kv_offset(g.kv, ri.seq, ri.slot, kvh);
+        const size_t off = kv_offset(g.kv, rp.seq, rp.slot, kvh);
         void* base = hd < H + KVH ? g.kv.k : g.kv.v;
         if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
         else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
@@ -163,21 +203,27 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
   float ss = 0.f;
   for (int c = slot; c < nchunks; c += V2_THREADS / 32) {
     const int n = n0 + 8 * c;
-    float x[8], pv[8];
+    float x[8], pv[8], hv[8], bv[8], gv[8];
     int rows[8];
+    const float rw = g.row_w ? g.row_w[m] : 1.0f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) rows[t] = min(n + t, n1 - 1);
+    for (int t = 0; t < 8; ++t) {                            // everything that does not depend on the partials first
+      rows[t] = min(n + t, n1 - 1);
+      hv[t] = (g.h_in && live) ? g.h_in[(size_t)m * g.d + rows[t]] : 0.f;
+      bv[t] = g.bias ? g.bias[rows[t]] : 0.f;
+      gv[t] = g.gain_next ? g.gain_next[rows[t]] : 1.0f;
+    }
     pt_sum8(g.PT, g.S, g.Npad, rows, m, pv);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       float v = 0.f;
       if (n + t < n1) {
-        v = g.row_w ? g.row_w[m] * pv[t] : pv[t];
-        if (g.bias) v += g.bias[n + t];
-        if (g.h_in && live) v += g.h_in[(size_t)m * g.d + n + t];
+        v = g.row_w ? rw * pv[t] : pv[t];
+        if (g.bias) v += bv[t];
+        if (g.h_in && live) v += hv[t];
         if (live) g.h_out[(size_t)m * g.d + n + t] = v;
         ss += v * v;
-        x[t] = g.gain_next ? v * g.gain_next[n + t] : v;
+        x[t] = g.gain_next ? v * gv[t] : v;
       } else x[t] = 0.f;
     }
     if (live) xf_store8(g.xf_out, m, n, 1, g.xf_KS, NXP, x);
@@ -217,18 +263,11 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const flo
   }
 }
 
-__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/, const float* rstd_s) {
+__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/, const float* rstd_s, const RowPre& rp) {
   const int a = threadIdx.x & 31, b = threadIdx.x >> 5;        // read side: m = a, row b of 16
   const int a2 = threadIdx.x & 15, b2 = threadIdx.x >> 4;      // write side: n = a2, m = b2
   const float rs = a < g.M ? rstd_s[a] : 0.f;
-  long dst = -1;
-  if (b2 < g.M) {
-    RowInfo ri = row_info(g.pass, g.tree, g.st, b2);
-    if (ri.valid) {
-      if (g.out_kind == 0) { if (ri.node >= 0) dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
-      else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) dst = (long)ri.seq * g.V;
-    }
-  }
+  const long dst = rp.dst;
   for (int nb0 = n0; nb0 < n1; nb0 += 128) {                 // 8 x 16 rows per batch of loads
     int rows[8];
     float val[8];
@@ -356,6 +395,27 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   u32x4 pre[DEPTH * RW * NWP];
   if (!(g.dbg & 4)) k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
 
+  // row facts and the 1/rms inputs the epilogue will want: requested now, used (by the last work-group) much later
+  RowPre rp;
+  rp.valid = 0; rp.seq = 0; rp.pos = 0; rp.slot = 0; rp.dst = -1;
+  rp.ssq_part = rstd_class_partial(g.in_scale);
+  if (g.epi == EPI_QKV) {
+    const int m = threadIdx.x & 31;
+    if (m < g.M) {
+      const RowInfo ri = row_info(g.pass, g.tree, g.st, m);
+      rp.valid = ri.valid; rp.seq = ri.seq; rp.pos = ri.pos; rp.slot = ri.slot;
+    }
+  } else if (g.epi == EPI_LOGITS) {
+    const int b2 = threadIdx.x >> 4;
+    if (b2 < g.M) {
+      const RowInfo ri = row_info(g.pass, g.tree, g.st, b2);
+      if (ri.valid) {
+        if (g.out_kind == 0) { if (ri.node >= 0) rp.dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
+        else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) rp.dst = (long)ri.seq * g.V;
+      }
+    }
+  }
+
   // stage this work-group's K slice of X: per plane a contiguous run of kt tiles (8 loads in flight per thread)
   for (int p = 0; p < NXP; ++p) {
     const u32x4* src = (const u32x4*)(g.XF + ((size_t)p * g.KS + ks0) * 512);
@@ -427,12 +487,12 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
   if (n1 <= n0) return;
   __shared__ float rstd_s[32];
-  if (g.epi != EPI_RESID) block_rstd(g.in_scale, rstd_s, sh_small);
+  if (g.epi != EPI_RESID) block_rstd_finish(g.in_scale, rp.ssq_part, rstd_s, sh_small);
   switch (g.epi) {
-    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1, rstd_s); break;
+    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1, rstd_s, rp); break;
     case EPI_RESID: epilogue_resid<NXP>(g, grp, n0, n1, sh_small); break;
     case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
-    default: epilogue_logits(g, n0, n1, sh_small, rstd_s); break;
+    default: epilogue_logits(g, n0, n1, sh_small, rstd_s, rp); break;
   }
 }
 
