@@ -130,7 +130,12 @@ enum {
   EAGLE_BUF_TOKENS,            /* int32 [n committed tokens] the slot's whole token sequence               */
   EAGLE_BUF_VANILLA_LOGITS,    /* fp32 [vocab]              logits of the last eagle_vanilla_step / prefill */
   EAGLE_BUF_STATE,             /* int32 [4]: committed tokens, cached target positions, pending features, steps */
-  EAGLE_BUF_KV_ROW             /* see eagle_get_kv_row                                                      */
+  EAGLE_BUF_KV_ROW,            /* see eagle_get_kv_row                                                      */
+  EAGLE_BUF_GEMM_TRACE         /* uint64 [1024 work-groups][8 events]: 100 MHz time stamps of ONE launch of the
+                                  weight-streaming GEMM kernel, selected with the environment variable
+                                  EAGLE_GEMM_TRACE=<index of the launch within the verify phase> (read by eagle_init);
+                                  events: 0 entered, 1 activations staged, 2 weight stream done, 3 partial sums
+                                  published, 4 epilogue done (the work-groups that ran one).  Zero where unset. */
 };
 int eagle_get_buffer(eagle_ctx *ctx, int32_t which, int32_t seq, void *host_dst, size_t cap_bytes);
 /* K and V (fp32, [n_kv_heads*head_dim] each) of target layer `layer` (or EAGLE_HEAD_LAYER) at cache position pos. */

@@ -19,7 +19,7 @@ HEAD_LAYER = -1
 (W_EMBED, W_LM_HEAD, W_FINAL_NORM, W_FC, W_FC_BIAS, W_ATTN_NORM, W_Q, W_K, W_V, W_O, W_MLP_NORM, W_ROUTER,
  W_GATE, W_UP, W_DOWN) = range(15)
 (BUF_LOGITS, BUF_FEATURES, BUF_DRAFT_LOGITS, BUF_DRAFT_FEATURES, BUF_TREE_TOKENS, BUF_TOKENS, BUF_VANILLA_LOGITS,
- BUF_STATE) = range(8)
+ BUF_STATE, BUF_KV_ROW, BUF_GEMM_TRACE) = range(10)
 
 _LAYER_IDS = {"attn_norm": W_ATTN_NORM, "wq": W_Q, "wk": W_K, "wv": W_V, "wo": W_O, "mlp_norm": W_MLP_NORM,
               "router": W_ROUTER, "gate": W_GATE, "up": W_UP, "down": W_DOWN}
@@ -261,6 +261,8 @@ class Eagle:
         elif which == BUF_TOKENS:
             n = int(self.get_buffer(BUF_STATE, seq)[0])
             out = np.empty(n, np.int32)
+        elif which == BUF_GEMM_TRACE:
+            out = np.zeros((1024, 8), np.uint64)
         else:
             raise ValueError(which)
         self._chk(self.lib.eagle_get_buffer(self.h, which, seq, out.ctypes.data, out.nbytes))

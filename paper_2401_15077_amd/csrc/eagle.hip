@@ -83,6 +83,7 @@ struct eagle_ctx {
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
   float *moe_w, *xn; int* expert_used;    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
+  unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
   int n_cu = 256;
   // host mirror
   std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
@@ -295,6 +296,7 @@ static size_t layout(eagle_ctx* c) {
   c->xf2_att = a.take<bf16_t>((size_t)c->NXP * 32 * H * dh);
   c->xf2_ffn = a.take<bf16_t>((size_t)c->NXP * 32 * F);
   c->ssq1 = a.take<float>(256 * 32); c->ssq2 = a.take<float>(256 * 32);
+  c->trace = a.take<unsigned long long>(1024 * 8);
   c->cnt_gemm = a.take<int>(1024); c->cnt_attn = a.take<int>((size_t)64 * H);
   size_t worst2 = 0;
   auto consider2 = [&](const PackedW& w) {
@@ -390,6 +392,8 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   for (int i = 0; i < 4; ++i)
     if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "event creation failed"); }
   memset(&c->prof, 0, sizeof(c->prof));
+  if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
+  if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   *out = c;
   return EAGLE_OK;
 }
@@ -680,6 +684,7 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   g.XF = XF; g.S = p.S; g.groups = p.groups; g.lanes = p.lanes; g.kparts = p.kparts;
   g.PT = c->PT2; g.counters = c->cnt_gemm;
   { static int dbg = -1; if (dbg < 0) { const char* e = getenv("EAGLE_DEBUG_GEMM"); dbg = e ? atoi(e) : 0; } g.dbg = dbg; }
+  g.trace = (c->gemm_no++ == c->trace_sel && p.groups * p.S <= 1024) ? c->trace : nullptr;
   if (g.ssq_out && p.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
   if (groups_out) *groups_out = p.groups;
   bool timed = c->prof_mode == 2;
@@ -735,6 +740,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   if ((rc = gemm2(c, w.qkv, c->xf2_d, g, nullptr))) return rc;
   {
     int n_splits = std::max(1, std::min(16, (ctx_max + 64 + 127) / 128));   // 128 tokens = one 32-token block per wave
+    unsigned long long* atrace = (c->attn_no++ == c->attn_trace_sel && n_splits * H <= 1024) ? c->trace : nullptr;
     dim3 grid(n_splits, H, pass.n_seq);
     float scale = 1.0f / std::sqrt((float)dh);
     KVCache kv = kv_for(c, li);
@@ -746,7 +752,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
       attr_done = true;                                                                                                 \
     }                                                                                                                   \
     k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
-        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP); \
+        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP, atrace); \
   } while (0)
     if (c->kv_f32) { if (dh == 128) ATTN2(float, 128); else if (dh == 64) ATTN2(float, 64); else ATTN2(float, 32); }
     else { if (dh == 128) ATTN2(bf16_t, 128); else if (dh == 64) ATTN2(bf16_t, 64); else ATTN2(bf16_t, 32); }
@@ -941,6 +947,7 @@ static int do_draft(eagle_ctx* c) {
 
 static int do_verify(eagle_ctx* c) {
   if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
+  c->gemm_no = 0; c->attn_no = 0;
   Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
   int rc = c->M * c->n_active <= 32 ? target_forward2(c, pv, max_ctx(c), c->M, c->L, 0)
                                     : target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
@@ -1111,6 +1118,7 @@ extern "C" int eagle_get_buffer(eagle_ctx* c, int32_t which, int32_t seq, void* 
       memcpy(dst, state, sizeof(state));
       return EAGLE_OK;
     }
+    case EAGLE_BUF_GEMM_TRACE: src = c->trace; bytes = (size_t)1024 * 8 * 8; break;
     default: return fail(EAGLE_EINVAL, "unknown buffer id %d", which);
   }
   if (cap < bytes) return fail(EAGLE_EINVAL, "destination of %zu bytes is smaller than the %zu needed", cap, bytes);

@@ -21,6 +21,22 @@
 __device__ inline void coh_store(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ inline float coh_load(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
+// 16-byte agent-scope accesses: buffer instructions carry the scope bit (aux 16 = sc1); byte offsets below 2 GiB.
+__device__ inline __amdgpu_buffer_rsrc_t coh_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, 0x7FFFFFFF, 0x00020000);
+}
+__device__ inline f32x4 coh_load16(const void* base, uint32_t byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(coh_rsrc(base), byte_off, 0, 16));
+}
+__device__ inline void coh_store16(void* base, uint32_t byte_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), coh_rsrc(base), byte_off, 0, 16);
+}
+// Split-K partials PT[s][n][m]: four consecutive weight rows n of one token m are adjacent (16 bytes), which is what
+// one lane of the MFMA accumulator holds (registers 4i..4i+3) and what an epilogue thread consumes.
+__device__ inline uint32_t pt_quad_bytes(int s, int Npad, int n4 /*multiple of 4*/, int m) {
+  return (uint32_t)((((size_t)s * Npad + n4) * 32 + (size_t)m * 4) * 4);
+}
+
 struct RowScale {            // 1/rms of the rows that produced the GEMM input; ssq == nullptr -> 1
   const float* ssq;          // [groups][32] partial sums of squares
   int groups;
@@ -114,35 +130,35 @@ struct Gemm2 {
   float* logits; int out_kind, V, only_last_row;
   const float* row_w;                     // MoE: per-row routing weight applied to this GEMM's result (nullptr = 1)
   const int* skip_flag;                   // MoE: the whole launch is a no-op when *skip_flag == 0 (no row uses the expert)
+  unsigned long long* trace;              // optional [work-group][8] time stamps (100 MHz wall clock) of this launch
   int dbg;                                // timing experiments only (0 in normal use): 1 = no epilogue, 2 = stop after the main loop, 4 = no main loop
 };
 
-// out[t] = sum over the K splits of PT[s][rows[t]][m], t < 8: eight coherent loads in flight per split, splits
-// added in order (the loads are agent-scope atomics, which the compiler will not hoist above one another's uses
-// unless they are issued together like this).
+// out[0..3] = sum over the K splits of rows nA..nA+3, out[4..7] the same for rows nB..nB+3 (nA, nB multiples of 4,
+// below Npad), token m.  All loads of a batch of splits are in flight together; splits are added in order.
 template <int B>
-__device__ inline void pt_sum8_b(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
-  for (int s0 = 0; s0 < S; s0 += B) {                        // B splits x 8 rows in flight
-    float v[B][8];
+__device__ inline void pt_sum8_b(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int m, float* out) {
+  for (int s0 = 0; s0 < S; s0 += B) {
+    f32x4 va[B], vb[B];
 #pragma unroll
     for (int u = 0; u < B; ++u) {
       const int s = min(s0 + u, S - 1);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[u][t] = coh_load(PT + ((size_t)s * Npad + rows[t]) * 32 + m);
+      va[u] = coh_load16(PT, pt_quad_bytes(s, Npad, nA, m));
+      vb[u] = coh_load16(PT, pt_quad_bytes(s, Npad, nB, m));
     }
 #pragma unroll
     for (int u = 0; u < B; ++u)
       if (s0 + u < S) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t] += v[u][t];
+        out[0] += va[u].x; out[1] += va[u].y; out[2] += va[u].z; out[3] += va[u].w;
+        out[4] += vb[u].x; out[5] += vb[u].y; out[6] += vb[u].z; out[7] += vb[u].w;
       }
   }
 }
-__device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, const int* rows, int m, float* out) {
+__device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int m, float* out) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) out[t] = 0.f;
-  if (S <= 4) pt_sum8_b<4>(PT, S, Npad, rows, m, out);
-  else pt_sum8_b<16>(PT, S, Npad, rows, m, out);
+  if (S <= 4) pt_sum8_b<4>(PT, S, Npad, nA, nB, m, out);
+  else pt_sum8_b<16>(PT, S, Npad, nA, nB, m, out);
 }
 
 // what a thread needs about "its" row in the epilogue, fetched before the streaming loop so that the loads are
@@ -155,25 +171,25 @@ __device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float*
   const int dh = g.kv.head_dim, half = dh >> 1, KVH = g.kv.n_kv_heads, H = g.H;
   const bool live = m < g.M;
   const float rs = live ? rstd_s[m] : 0.f;
-  const int npairs = (n1 - n0) >> 1;
+  const int nquads = (n1 - n0) >> 2;                          // n0, n1 are multiples of 32 here (whole heads)
   constexpr int SL = V2_THREADS / 32;
-  for (int p0 = slot; p0 < npairs; p0 += 4 * SL) {          // four pairs (eight rows) per batch
-    int rows[8];
+  for (int q0 = slot; q0 < nquads; q0 += 2 * SL) {           // two quads = four rotate-half pairs per batch
+    const int qa = q0, qb = min(q0 + SL, nquads - 1);
+    const int nq[2] = {n0 + 4 * qa, n0 + 4 * qb};
     float cs[4], sn[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int p = min(p0 + u * SL, npairs - 1);
-      rows[2 * u] = n0 + 2 * p; rows[2 * u + 1] = n0 + 2 * p + 1;
-      const int i = (rows[2 * u] % dh) >> 1;                 // rotation angle index (unused for v heads)
+      const int n = nq[u >> 1] + 2 * (u & 1);
+      const int i = (n % dh) >> 1;                            // rotation angle index (unused for v heads)
       cs[u] = g.rope_cos[(size_t)rp.pos * half + i];
       sn[u] = g.rope_sin[(size_t)rp.pos * half + i];
     }
     float val[8];
-    pt_sum8(g.PT, g.S, g.Npad, rows, m, val);
+    pt_sum8(g.PT, g.S, g.Npad, nq[0], nq[1], m, val);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      if (p0 + u * SL >= npairs || !live) continue;
-      const int n = rows[2 * u], hd = n / dh, pr = n % dh;
+      if ((u >= 2 && q0 + SL >= nquads) || !live) continue;
+      const int n = nq[u >> 1] + 2 * (u & 1), hd = n / dh, pr = n % dh;
       float a = val[2 * u] * rs, b = val[2 * u + 1] * rs;
       int d1, d2;
       if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
@@ -213,7 +229,7 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
       bv[t] = g.bias ? g.bias[rows[t]] : 0.f;
       gv[t] = g.gain_next ? g.gain_next[rows[t]] : 1.0f;
     }
-    pt_sum8(g.PT, g.S, g.Npad, rows, m, pv);
+    pt_sum8(g.PT, g.S, g.Npad, n, n + 4, m, pv);            // rows up to the padded end of the block exist (zero weights)
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       float v = 0.f;
@@ -249,11 +265,8 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const flo
     const int nb = n0 + rb * 32 + 8 * c2;            // gate rows; the matching up rows are 16 further
     const int f = ((n0 >> 5) + rb) * 16 + 8 * c2;
     float x[8], gv[8], uv[8];
-    int rg_[8], ru_[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) { rg_[t] = nb + t; ru_[t] = nb + 16 + t; }
-    pt_sum8(g.PT, g.S, g.Npad, rg_, m, gv);
-    pt_sum8(g.PT, g.S, g.Npad, ru_, m, uv);
+    pt_sum8(g.PT, g.S, g.Npad, nb, nb + 4, m, gv);
+    pt_sum8(g.PT, g.S, g.Npad, nb + 16, nb + 20, m, uv);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float gg = gv[t] * rs, uu = uv[t] * rs;
@@ -263,24 +276,28 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const flo
   }
 }
 
-__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, float* sh /*>= 16*33 floats*/, const float* rstd_s, const RowPre& rp) {
-  const int a = threadIdx.x & 31, b = threadIdx.x >> 5;        // read side: m = a, row b of 16
-  const int a2 = threadIdx.x & 15, b2 = threadIdx.x >> 4;      // write side: n = a2, m = b2
-  const float rs = a < g.M ? rstd_s[a] : 0.f;
-  const long dst = rp.dst;
-  for (int nb0 = n0; nb0 < n1; nb0 += 128) {                 // 8 x 16 rows per batch of loads
-    int rows[8];
+__device__ inline void epilogue_logits(const Gemm2& g, int n0, int n1, const float* rstd_s, const RowPre& rp) {
+  const int m = threadIdx.x & 31, b = threadIdx.x >> 5;        // token m, quad b (and b + 16) of each 128-row batch
+  const float rs = m < g.M ? rstd_s[m] : 0.f;
+  const long dst = rp.dst;                                     // where token m's logits row starts, or -1
+  const int nend = min(n1, g.V);
+  const bool vec = (g.V & 3) == 0;                             // rows of the output are 16-byte aligned
+  for (int nb0 = n0; nb0 < n1; nb0 += 128) {
+    const int nA = nb0 + 4 * b, nB = nb0 + 64 + 4 * b;
     float val[8];
+    pt_sum8(g.PT, g.S, g.Npad, min(nA, g.Npad - 4), min(nB, g.Npad - 4), m, val);
+    if (dst < 0) continue;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rows[i] = min(nb0 + 16 * i + b, n1 - 1);
-    pt_sum8(g.PT, g.S, g.Npad, rows, a, val);
+    for (int h = 0; h < 2; ++h) {
+      const int n = h ? nB : nA;
+      if (n >= nend) continue;
+      if (vec && n + 4 <= nend) {
+        f32x4 o; o.x = val[4 * h] * rs; o.y = val[4 * h + 1] * rs; o.z = val[4 * h + 2] * rs; o.w = val[4 * h + 3] * rs;
+        *(f32x4*)(g.logits + dst + n) = o;
+      } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int nb = nb0 + 16 * i;
-      sh[b * 33 + a] = (nb + b < n1 && a < g.M) ? val[i] * rs : 0.f;
-      __syncthreads();
-      if (dst >= 0 && nb + a2 < n1 && nb + a2 < g.V) g.logits[dst + nb + a2] = sh[a2 * 33 + b2];
-      __syncthreads();
+        for (int t = 0; t < 4; ++t) if (n + t < nend) g.logits[dst + n + t] = val[4 * h + t] * rs;
+      }
     }
   }
 }
@@ -375,11 +392,15 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   if (g.skip_flag && *g.skip_flag == 0) return;               // uniform over the whole grid
   u32x4* xs = (u32x4*)smem;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int s = blockIdx.x % g.S, grp = blockIdx.x / g.S;
-  const int rb0 = (int)((long)grp * g.NRB / g.groups), rb1 = (int)((long)(grp + 1) * g.NRB / g.groups);
-  const int ks0 = (int)((long)s * g.KS / g.S), ks1 = (int)((long)(s + 1) * g.KS / g.S), kt = ks1 - ks0;
-  const int la = w % g.lanes, kb_i = w / g.lanes;
-  const int kb = (int)((long)kb_i * kt / g.kparts), ke = (int)((long)(kb_i + 1) * kt / g.kparts);
+  // the work split in 32-bit arithmetic: every product stays far below 2^31 (<= 1024 groups x a few thousand row blocks)
+  const unsigned uS = g.S, ugroups = g.groups, uNRB = g.NRB, uKS = g.KS, ulanes = g.lanes, ukparts = g.kparts;
+  const int s = blockIdx.x % uS, grp = blockIdx.x / uS;
+  const int rb0 = (unsigned)grp * uNRB / ugroups, rb1 = (unsigned)(grp + 1) * uNRB / ugroups;
+  const int ks0 = (unsigned)s * uKS / uS, ks1 = (unsigned)(s + 1) * uKS / uS, kt = ks1 - ks0;
+  const int la = (unsigned)w % ulanes, kb_i = (unsigned)w / ulanes;
+  const int kb = (unsigned)kb_i * (unsigned)kt / ukparts, ke = (unsigned)(kb_i + 1) * (unsigned)kt / ukparts;
+  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
+  if (tr) tr[0] = wall_clock64();
   int nr = 0;
   for (int j = 0; j < RW; ++j) nr += (rb0 + la + j * g.lanes < rb1) ? 1 : 0;
   nr = __builtin_amdgcn_readfirstlane(nr);
@@ -406,9 +427,9 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
       rp.valid = ri.valid; rp.seq = ri.seq; rp.pos = ri.pos; rp.slot = ri.slot;
     }
   } else if (g.epi == EPI_LOGITS) {
-    const int b2 = threadIdx.x >> 4;
-    if (b2 < g.M) {
-      const RowInfo ri = row_info(g.pass, g.tree, g.st, b2);
+    const int m = threadIdx.x & 31;
+    if (m < g.M) {
+      const RowInfo ri = row_info(g.pass, g.tree, g.st, m);
       if (ri.valid) {
         if (g.out_kind == 0) { if (ri.node >= 0) rp.dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
         else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) rp.dst = (long)ri.seq * g.V;
@@ -438,7 +459,9 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   __syncthreads();
+  if (tr) tr[1] = wall_clock64();
   if (!(g.dbg & 4)) k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane, pre);
+  if (tr) tr[2] = wall_clock64();
   if (g.dbg & 2) { if (acc[0][0] == 123.456f) g.PT[0] = 1.f; return; }
   // waves that split K inside the work-group: sum through LDS in k-part order
   if (g.kparts > 1) {
@@ -468,9 +491,11 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     for (int j = 0; j < RW; ++j)
       if (j < nr) {
         const int rb = rb0 + la + j * g.lanes;
-        float* out = g.PT + ((size_t)s * g.Npad + (size_t)rb * 32) * 32;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) coh_store(out + (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 32 + (lane & 31), acc[j][r]);
+        for (int i = 0; i < 4; ++i) {                           // accumulator registers 4i..4i+3 = rows 8i + 4(lane/32) + 0..3
+          f32x4 v; v.x = acc[j][4 * i]; v.y = acc[j][4 * i + 1]; v.z = acc[j][4 * i + 2]; v.w = acc[j][4 * i + 3];
+          coh_store16(g.PT, pt_quad_bytes(s, g.Npad, rb * 32 + 8 * i + 4 * (lane >> 5), lane & 31), v);
+        }
       }
   }
   // publish the partials; the last work-group of this row group to arrive finishes the job
@@ -482,6 +507,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     if (s_last) __hip_atomic_store(g.counters + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
+  if (tr) tr[3] = wall_clock64();
   if (!s_last || (g.dbg & 1)) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
@@ -492,8 +518,9 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1, rstd_s, rp); break;
     case EPI_RESID: epilogue_resid<NXP>(g, grp, n0, n1, sh_small); break;
     case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
-    default: epilogue_logits(g, n0, n1, sh_small, rstd_s, rp); break;
+    default: epilogue_logits(g, n0, n1, rstd_s, rp); break;
   }
+  if (tr) tr[4] = wall_clock64();
 }
 
 // Rows of a pass that need no GEMM in front: h = embedding of the row's token.  Writes h, XF(h * gain) and the
@@ -581,7 +608,7 @@ template <typename CT, int DH>
 __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
                                                const float* __restrict__ Q, float* part_o, float* part_ml, int H,
                                                int n_splits, int n_new, float scale, int* counters, bf16_t* xf_out,
-                                               int nplanes) {
+                                               int nplanes, unsigned long long* trace) {
   constexpr int KSN = DH / 16;              // k-steps of the QK product
   constexpr int DB = DH / 32;               // 32-wide blocks of the head dimension
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_a[];
@@ -589,6 +616,9 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   float* ml_s = o_s + 4 * DH * 32;          // [4 waves][2][32]
   __shared__ int s_last;
   const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z;
+  // optional time stamps: 0 entered, 1 keys/values consumed, 2 waves merged + partials written, 3 arrived, 4 splits merged
+  unsigned long long* tr = (trace && threadIdx.x == 0 && seq_l == 0) ? trace + ((size_t)hd * gridDim.x + split) * 8 : nullptr;
+  if (tr) tr[0] = wall_clock64();
   const int r0 = seq_l * pass.rows_per_seq;
   const int R = min(32, pass.rows_per_seq);
   const int kvh = hd / (H / kv.n_kv_heads);
@@ -703,6 +733,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
       }
     }
   }
+  if (tr) tr[1] = wall_clock64();
   // merge the 4 waves through LDS: o_s[w][d][q], d = 32b + 8(r/4) + 4hh + r%4
 #pragma unroll
   for (int b = 0; b < DB; ++b)
@@ -739,11 +770,14 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
       for (int t = 0; t < 8; ++t) o[t] *= inv;
       xf_store8(xf_out, r0 + q2, hd * DH + 8 * c, 1, KSX, nplanes, o);
     } else {
-      float* po = part_o + (((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + 8 * c;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) coh_store(po + i, o[i]);
+      const uint32_t po = (uint32_t)(((((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + 8 * c) * 4);
+      f32x4 v0, v1;
+      v0.x = o[0]; v0.y = o[1]; v0.z = o[2]; v0.w = o[3]; v1.x = o[4]; v1.y = o[5]; v1.z = o[6]; v1.w = o[7];
+      coh_store16(part_o, po, v0);
+      coh_store16(part_o, po + 16, v1);
     }
   }
+  if (tr) tr[2] = wall_clock64();
   if (n_splits == 1) return;
   if (q2 < R && tid < 32) {
     const size_t ofs = (((size_t)(r0 + q2) * H + hd) * n_splits + split) * 2;
@@ -759,49 +793,54 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     if (s_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
+  if (tr) tr[3] = wall_clock64();
   if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  // merge the splits of (sequence, head): thread = (row, 8-wide column chunk)
-  for (int it = tid; it < R * (DH / 8); it += 256) {
-    const int r = it / (DH / 8), d0 = (it % (DH / 8)) * 8;
-    const float* ml = part_ml + ((size_t)(r0 + r) * H + hd) * n_splits * 2;
-    float msv[16], lsv[16];
+  // merge the splits of (sequence, head): thread = (row, CW-wide column chunk), one item per thread in the usual
+  // shapes.  Every load of up to 8 splits -- (max, sum) pairs and partial outputs -- is in flight at once, so the
+  // merge costs one memory round trip; more splits continue with a running rescale, in split order.
+  constexpr int CW = DH >= 128 ? 16 : 8, NQ = CW / 4;
+  for (int it = tid; it < R * (DH / CW); it += 256) {
+    const int r = it / (DH / CW), d0 = (it % (DH / CW)) * CW;
+    const size_t rowhead = ((size_t)(r0 + r) * H + hd) * n_splits;
+    float mx = -INFINITY, den = 0.f, x[CW];
 #pragma unroll
-    for (int sp = 0; sp < 16; ++sp) {                          // all (max, sum) pairs in flight at once
-      const int qq = min(sp, n_splits - 1);
-      msv[sp] = coh_load(ml + 2 * qq);
-      lsv[sp] = coh_load(ml + 2 * qq + 1);
-    }
-    float mx = -INFINITY;
+    for (int t = 0; t < CW; ++t) x[t] = 0.f;
+    for (int sp0 = 0; sp0 < n_splits; sp0 += 8) {
+      float msv[8], lsv[8];
+      f32x4 ov[8][NQ];
 #pragma unroll
-    for (int sp = 0; sp < 16; ++sp) if (sp < n_splits) mx = fmaxf(mx, msv[sp]);
-    float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    float wv[16];
+      for (int u = 0; u < 8; ++u) {
+        const size_t e = rowhead + min(sp0 + u, n_splits - 1);
+        msv[u] = coh_load(part_ml + e * 2);
+        lsv[u] = coh_load(part_ml + e * 2 + 1);
 #pragma unroll
-    for (int sp = 0; sp < 16; ++sp) {
-      wv[sp] = (sp < n_splits && msv[sp] != -INFINITY) ? __expf(msv[sp] - mx) : 0.f;
-      den += wv[sp] * lsv[sp];
-    }
-    for (int sp0 = 0; sp0 < n_splits; sp0 += 4) {              // 4 splits x 8 values in flight, added in split order
-      float ov[4][8];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int qq = min(sp0 + u, n_splits - 1);
-        const float* op = part_o + (((size_t)(r0 + r) * H + hd) * n_splits + qq) * DH + d0;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) ov[u][t] = coh_load(op + t);
+        for (int qd = 0; qd < NQ; ++qd) ov[u][qd] = coh_load16(part_o, (uint32_t)((e * DH + d0 + 4 * qd) * 4));
       }
+      float cmx = mx;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        float wg2 = 0.f;
+      for (int u = 0; u < 8; ++u) if (sp0 + u < n_splits) cmx = fmaxf(cmx, msv[u]);
+      const float resc = (mx == -INFINITY) ? 0.f : __expf(mx - cmx);   // 1 on the first chunk's empty history
+      den *= resc;
 #pragma unroll
-        for (int qq = 0; qq < 16; ++qq) if (qq == sp0 + u) wg2 = wv[qq];
+      for (int t = 0; t < CW; ++t) x[t] *= resc;
+      mx = cmx;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] += wg2 * ov[u][t];
+      for (int u = 0; u < 8; ++u) {
+        const float wv = (sp0 + u < n_splits && msv[u] != -INFINITY) ? __expf(msv[u] - mx) : 0.f;
+        den += wv * lsv[u];
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd) {
+          x[4 * qd] += wv * ov[u][qd].x; x[4 * qd + 1] += wv * ov[u][qd].y;
+          x[4 * qd + 2] += wv * ov[u][qd].z; x[4 * qd + 3] += wv * ov[u][qd].w;
+        }
       }
     }
     const float inv = den > 0.f ? 1.0f / den : 0.f;
-    for (int t = 0; t < 8; ++t) x[t] *= inv;
-    xf_store8(xf_out, r0 + r, hd * DH + d0, 1, KSX, nplanes, x);
+#pragma unroll
+    for (int t = 0; t < CW; ++t) x[t] *= inv;
+#pragma unroll
+    for (int h8 = 0; h8 < CW / 8; ++h8) xf_store8(xf_out, r0 + r, hd * DH + d0 + 8 * h8, 1, KSX, nplanes, x + 8 * h8);
   }
+  if (tr) tr[4] = wall_clock64();
 }
