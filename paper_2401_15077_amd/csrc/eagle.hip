@@ -114,7 +114,7 @@ static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
   Plan2 p;
   const int x_cap_kb = 128;                                   // LDS given to the X slice / the wave reduction
   int S = 1;
-  while ((NXP * ((KS + S - 1) / S)) > x_cap_kb) S *= 2;
+  while ((NXP * ((KS + S - 1) / S)) > x_cap_kb) ++S;          // fewest K slices whose X slice fits (fewer partials to exchange)
   int groups = std::max(1, std::min(NRB, n_cu / S));
   // few row blocks: split K further (slices of at least 4 k-steps) until the grid fills the chip
   while (groups * S * 2 <= n_cu && (KS + 2 * S - 1) / (2 * S) >= 4) S *= 2;

@@ -161,6 +161,30 @@ __device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, in
   else pt_sum8_b<16>(PT, S, Npad, nA, nB, m, out);
 }
 
+// four quads at once (S <= 4: 16 loads in flight; more splits: two rounds of two quads)
+__device__ inline void pt_sum16(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int nC, int nD, int m, float* outAB, float* outCD) {
+  if (S > 4) { pt_sum8(PT, S, Npad, nA, nB, m, outAB); pt_sum8(PT, S, Npad, nC, nD, m, outCD); return; }
+  f32x4 v[4][4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int sp = min(u, S - 1);
+    v[u][0] = coh_load16(PT, pt_quad_bytes(sp, Npad, nA, m));
+    v[u][1] = coh_load16(PT, pt_quad_bytes(sp, Npad, nB, m));
+    v[u][2] = coh_load16(PT, pt_quad_bytes(sp, Npad, nC, m));
+    v[u][3] = coh_load16(PT, pt_quad_bytes(sp, Npad, nD, m));
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) { outAB[t] = 0.f; outCD[t] = 0.f; }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (u < S) {
+      outAB[0] += v[u][0].x; outAB[1] += v[u][0].y; outAB[2] += v[u][0].z; outAB[3] += v[u][0].w;
+      outAB[4] += v[u][1].x; outAB[5] += v[u][1].y; outAB[6] += v[u][1].z; outAB[7] += v[u][1].w;
+      outCD[0] += v[u][2].x; outCD[1] += v[u][2].y; outCD[2] += v[u][2].z; outCD[3] += v[u][2].w;
+      outCD[4] += v[u][3].x; outCD[5] += v[u][3].y; outCD[6] += v[u][3].z; outCD[7] += v[u][3].w;
+    }
+}
+
 // what a thread needs about "its" row in the epilogue, fetched before the streaming loop so that the loads are
 // long finished when the last work-group gets there
 struct RowPre { int valid, seq, pos, slot; long dst; float ssq_part; };
@@ -265,8 +289,7 @@ __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const flo
     const int nb = n0 + rb * 32 + 8 * c2;            // gate rows; the matching up rows are 16 further
     const int f = ((n0 >> 5) + rb) * 16 + 8 * c2;
     float x[8], gv[8], uv[8];
-    pt_sum8(g.PT, g.S, g.Npad, nb, nb + 4, m, gv);
-    pt_sum8(g.PT, g.S, g.Npad, nb + 16, nb + 20, m, uv);
+    pt_sum16(g.PT, g.S, g.Npad, nb, nb + 4, nb + 16, nb + 20, m, gv, uv);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float gg = gv[t] * rs, uu = uv[t] * rs;
