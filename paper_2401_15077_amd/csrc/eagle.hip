@@ -914,6 +914,14 @@ static int step_ready(eagle_ctx* c) {
   }
   return EAGLE_OK;
 }
+// Gives a decode-time pass the cached lengths the host mirrors (at most 4 sequences).
+static void pass_ctx(eagle_ctx* c, Pass& p) {
+  p.ctx_known = 0;
+  if (p.n_seq > 4) return;
+  int v[4] = {0, 0, 0, 0};
+  for (int i = 0; i < p.n_seq; ++i) v[i] = c->h_ctx[p.seq0 + i];
+  p.ctx_known = 1; p.ctx0 = v[0]; p.ctx1 = v[1]; p.ctx2 = v[2]; p.ctx3 = v[3];
+}
 static int max_ctx(eagle_ctx* c) {
   int m = 0;
   for (int s = 0; s < c->n_active; ++s) m = std::max(m, c->h_ctx[s]);
@@ -928,6 +936,7 @@ static int do_draft(eagle_ctx* c) {
   const int B = c->n_active, D1 = c->D + 1, ctx = max_ctx(c);
   const eagle_config& g = c->cfg;
   Pass p1{PASS_DRAFT_PENDING, D1, B, 0, 0, 0, 0};
+  pass_ctx(c, p1);
   if ((rc = (D1 * B <= 32 ? head_forward2(c, p1, ctx, D1) : head_forward(c, p1, ctx + D1, D1, true)))) return rc;
   dim3 g0(1, B);
   k_expand<<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
@@ -936,6 +945,7 @@ static int do_draft(eagle_ctx* c) {
     int nr = c->tree_h.n_level_rows[lev];
     if (nr == 0) break;
     Pass pl{PASS_DRAFT_LEVEL, nr, B, 0, lev, 0, 0};
+    pass_ctx(c, pl);
     if ((rc = (nr * B <= 32 ? head_forward2(c, pl, ctx, c->M) : head_forward(c, pl, ctx + c->M, c->M, true)))) return rc;
     dim3 gl(nr, B);
     k_expand<<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
@@ -949,6 +959,7 @@ static int do_verify(eagle_ctx* c) {
   if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
   c->gemm_no = 0; c->attn_no = 0;
   Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
+  pass_ctx(c, pv);
   int rc = c->M * c->n_active <= 32 ? target_forward2(c, pv, max_ctx(c), c->M, c->L, 0)
                                     : target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
   if (rc) return rc;
@@ -1051,6 +1062,7 @@ extern "C" int eagle_vanilla_step(eagle_ctx* c, int32_t* tokens) {
   const eagle_config& g = c->cfg;
   const int B = c->n_active;
   Pass pv{PASS_VANILLA, 1, B, 0, 0, 0, 0};
+  pass_ctx(c, pv);
   if ((rc = (B <= 32 ? target_forward2(c, pv, max_ctx(c), 1, c->vanilla_logits, 1)
                      : target_forward(c, pv, max_ctx(c) + 1, 1, true, c->vanilla_logits, 1, 0)))) return rc;
   k_choose<<<B, 1024, 0, c->stream>>>(c->st, 0, c->vanilla_logits, g.vocab, g.temperature, g.seed, c->pbuf, 0, 0, c->D);

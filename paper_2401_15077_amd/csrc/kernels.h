@@ -26,6 +26,9 @@ struct SeqState {          // all device pointers, one entry per sequence slot
 enum { PASS_VERIFY = 0, PASS_VANILLA, PASS_DRAFT_PENDING, PASS_DRAFT_LEVEL, PASS_PREFILL_T, PASS_PREFILL_D };
 struct Pass {
   int kind, rows_per_seq, n_seq, seq0, level, chunk_start, chunk_n;
+  // cached target positions of sequences seq0..seq0+3 as the host knows them at launch (it mirrors the device value
+  // between calls); saves every kernel a dependent load at its start.  ctx_known = 0: read st.ctx_len instead.
+  int ctx_known, ctx0, ctx1, ctx2, ctx3;
 };
 struct RowInfo {
   int seq, valid, pos, slot, base, rel, node, causal;
@@ -37,7 +40,9 @@ __device__ inline RowInfo row_info(const Pass& p, const TreeDev* t, const SeqSta
   int i = r % p.rows_per_seq;
   o.seq = p.seq0 + r / p.rows_per_seq;
   o.valid = 1; o.causal = 0; o.node = -1; o.mask = 0;
-  int ctx = st.ctx_len[o.seq];
+  int ctx;
+  if (p.ctx_known) { const int j = o.seq - p.seq0; ctx = j == 0 ? p.ctx0 : j == 1 ? p.ctx1 : j == 2 ? p.ctx2 : p.ctx3; }
+  else ctx = st.ctx_len[o.seq];
   switch (p.kind) {
     case PASS_VERIFY:
       o.node = i; o.base = ctx; o.rel = i; o.pos = ctx + t->depth[i]; o.slot = ctx + i; o.mask = t->anc[i];
@@ -623,7 +628,6 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
                                                  int V, float temperature, unsigned long long rng_seed, float* scratch /*[seq][rows][V]*/) {
   __shared__ float shv[16];
   __shared__ int shi[16];
-  __shared__ int chosen[EAGLE_MAX_CHILD];
   const int seq = blockIdx.y;
   const int v = level < 0 ? 0 : tree->level_rows[level][blockIdx.x];
   const int M = tree->M;
@@ -640,36 +644,60 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
   int hinted = -1;
   if (on_path[seq * M + v] && pos_child < hint.n[seq]) {
     hinted = hint.future[(size_t)seq * hint.stride + pos_child];
-    if (threadIdx.x == 0) {
-      uint32_t k24 = rng_u24(rng_prefix(hint.seed[seq], PURPOSE_HINT, 0), (uint32_t)seq, 0, (uint32_t)pos_child);
-      bool hit = (float)k24 * 5.9604644775390625e-8f < hint.alpha[seq];
-      lg[hinted] += hit ? hint.bias[seq] : -hint.bias[seq];
-    }
   }
-  __syncthreads();
   const int nk = tree->nchild[v];
-  const float* score = lg;
-  if (temperature > 0.f) {
-    float* sc = scratch + ((size_t)seq * gridDim.x + blockIdx.x) * V;
-    unsigned long long pre = rng_prefix(rng_seed, PURPOSE_GUMBEL, (unsigned long long)st.step_no[seq]);
-    for (int j = threadIdx.x; j < V; j += blockDim.x) {
-      float u = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)j) + 0.5f) * 5.9604644775390625e-8f;
-      sc[j] = lg[j] / temperature - logf(-logf(u));
+  // One pass over the logits: every thread keeps the best nk of its own entries (sorted, ties to the lower token id),
+  // then nk block-wide rounds pick the overall best among the threads' current heads.  The knob's bias is applied on
+  // the fly (and written back by the thread that owns the hinted token, since later phases read the adjusted logits).
+  float adj = 0.f;
+  if (hinted >= 0) {
+    uint32_t k24 = rng_u24(rng_prefix(hint.seed[seq], PURPOSE_HINT, 0), (uint32_t)seq, 0, (uint32_t)pos_child);
+    adj = ((float)k24 * 5.9604644775390625e-8f < hint.alpha[seq]) ? hint.bias[seq] : -hint.bias[seq];
+  }
+  const bool gumbel = temperature > 0.f;
+  unsigned long long pre = 0ull;
+  if (gumbel) pre = rng_prefix(rng_seed, PURPOSE_GUMBEL, (unsigned long long)st.step_no[seq]);
+  float tv[EAGLE_MAX_CHILD];
+  int ti[EAGLE_MAX_CHILD];
+#pragma unroll
+  for (int q = 0; q < EAGLE_MAX_CHILD; ++q) { tv[q] = -INFINITY; ti[q] = 0x7fffffff; }
+  for (int j0 = 0; j0 < V; j0 += 8 * 1024) {                 // 8 entries per thread in flight
+    float x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * 1024 + (int)threadIdx.x;
+      x[u] = lg[min(j, V - 1)];
     }
-    score = sc;
-    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * 1024 + (int)threadIdx.x;
+      if (j >= V) continue;
+      float sc = x[u];
+      if (j == hinted) { sc += adj; lg[j] = sc; }
+      if (gumbel) {
+        float un = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)j) + 0.5f) * 5.9604644775390625e-8f;
+        sc = sc / temperature - logf(-logf(un));
+      }
+      // insert (sc, j) into the sorted list
+      float cv = sc; int ci = j;
+#pragma unroll
+      for (int q = 0; q < EAGLE_MAX_CHILD; ++q) {
+        const bool win = cv > tv[q] || (cv == tv[q] && ci < ti[q]);
+        const float ov = tv[q]; const int oi = ti[q];
+        if (win) { tv[q] = cv; ti[q] = ci; cv = ov; ci = oi; }
+      }
+    }
   }
   for (int r = 0; r < nk; ++r) {
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int j = threadIdx.x; j < V; j += blockDim.x) {
-      bool taken = false;
-      for (int q = 0; q < r; ++q) taken |= (chosen[q] == j);
-      if (!taken) better(bv, bi, score[j], j);
-    }
+    float bv = tv[0];
+    int bi = ti[0];
     block_argmax(bv, bi, shv, shi);
+    if (bi == ti[0]) {                                          // this thread's head won: advance its list
+#pragma unroll
+      for (int q = 0; q + 1 < EAGLE_MAX_CHILD; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
+      tv[EAGLE_MAX_CHILD - 1] = -INFINITY; ti[EAGLE_MAX_CHILD - 1] = 0x7fffffff;
+    }
     if (threadIdx.x == 0) {
-      chosen[r] = bi;
       int c = tree->child[v][r];
       tree_tok[seq * M + c] = bi;
       on_path[seq * M + c] = (hinted >= 0 && bi == hinted);

@@ -157,32 +157,44 @@ __device__ inline void pt_sum8_b(const float* __restrict__ PT, int S, int Npad, 
 __device__ inline void pt_sum8(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int m, float* out) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) out[t] = 0.f;
+  // the batch size closest above S: loads beyond S would be wasted traffic in an epilogue that one CU's bandwidth bounds
   if (S <= 4) pt_sum8_b<4>(PT, S, Npad, nA, nB, m, out);
+  else if (S <= 8) pt_sum8_b<8>(PT, S, Npad, nA, nB, m, out);
+  else if (S <= 12) pt_sum8_b<12>(PT, S, Npad, nA, nB, m, out);
   else pt_sum8_b<16>(PT, S, Npad, nA, nB, m, out);
 }
 
-// four quads at once (S <= 4: 16 loads in flight; more splits: two rounds of two quads)
-__device__ inline void pt_sum16(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int nC, int nD, int m, float* outAB, float* outCD) {
-  if (S > 4) { pt_sum8(PT, S, Npad, nA, nB, m, outAB); pt_sum8(PT, S, Npad, nC, nD, m, outCD); return; }
-  f32x4 v[4][4];
+// four quads at once, S <= 4: 16 loads in flight; issue and summation are separate so that a caller can put the
+// loads of several items in flight before it consumes the first
+struct PtQuads4 { f32x4 v[4][4]; };
+__device__ inline void pt_issue16(PtQuads4& b, const float* __restrict__ PT, int S, int Npad, int nA, int nB, int nC, int nD, int m) {
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int sp = min(u, S - 1);
-    v[u][0] = coh_load16(PT, pt_quad_bytes(sp, Npad, nA, m));
-    v[u][1] = coh_load16(PT, pt_quad_bytes(sp, Npad, nB, m));
-    v[u][2] = coh_load16(PT, pt_quad_bytes(sp, Npad, nC, m));
-    v[u][3] = coh_load16(PT, pt_quad_bytes(sp, Npad, nD, m));
+    b.v[u][0] = coh_load16(PT, pt_quad_bytes(sp, Npad, nA, m));
+    b.v[u][1] = coh_load16(PT, pt_quad_bytes(sp, Npad, nB, m));
+    b.v[u][2] = coh_load16(PT, pt_quad_bytes(sp, Npad, nC, m));
+    b.v[u][3] = coh_load16(PT, pt_quad_bytes(sp, Npad, nD, m));
   }
+}
+__device__ inline void pt_finish16(const PtQuads4& b, int S, float* outAB, float* outCD) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) { outAB[t] = 0.f; outCD[t] = 0.f; }
 #pragma unroll
   for (int u = 0; u < 4; ++u)
     if (u < S) {
-      outAB[0] += v[u][0].x; outAB[1] += v[u][0].y; outAB[2] += v[u][0].z; outAB[3] += v[u][0].w;
-      outAB[4] += v[u][1].x; outAB[5] += v[u][1].y; outAB[6] += v[u][1].z; outAB[7] += v[u][1].w;
-      outCD[0] += v[u][2].x; outCD[1] += v[u][2].y; outCD[2] += v[u][2].z; outCD[3] += v[u][2].w;
-      outCD[4] += v[u][3].x; outCD[5] += v[u][3].y; outCD[6] += v[u][3].z; outCD[7] += v[u][3].w;
+      outAB[0] += b.v[u][0].x; outAB[1] += b.v[u][0].y; outAB[2] += b.v[u][0].z; outAB[3] += b.v[u][0].w;
+      outAB[4] += b.v[u][1].x; outAB[5] += b.v[u][1].y; outAB[6] += b.v[u][1].z; outAB[7] += b.v[u][1].w;
+      outCD[0] += b.v[u][2].x; outCD[1] += b.v[u][2].y; outCD[2] += b.v[u][2].z; outCD[3] += b.v[u][2].w;
+      outCD[4] += b.v[u][3].x; outCD[5] += b.v[u][3].y; outCD[6] += b.v[u][3].z; outCD[7] += b.v[u][3].w;
     }
+}
+// the same for any S (more than 4 splits: two rounds of two quads)
+__device__ inline void pt_sum16(const float* __restrict__ PT, int S, int Npad, int nA, int nB, int nC, int nD, int m, float* outAB, float* outCD) {
+  if (S > 4) { pt_sum8(PT, S, Npad, nA, nB, m, outAB); pt_sum8(PT, S, Npad, nC, nD, m, outCD); return; }
+  PtQuads4 b;
+  pt_issue16(b, PT, S, Npad, nA, nB, nC, nD, m);
+  pt_finish16(b, S, outAB, outCD);
 }
 
 // what a thread needs about "its" row in the epilogue, fetched before the streaming loop so that the loads are
@@ -197,22 +209,23 @@ __device__ inline void epilogue_qkv(const Gemm2& g, int n0, int n1, const float*
   const float rs = live ? rstd_s[m] : 0.f;
   const int nquads = (n1 - n0) >> 2;                          // n0, n1 are multiples of 32 here (whole heads)
   constexpr int SL = V2_THREADS / 32;
-  for (int q0 = slot; q0 < nquads; q0 += 2 * SL) {           // two quads = four rotate-half pairs per batch
-    const int qa = q0, qb = min(q0 + SL, nquads - 1);
-    const int nq[2] = {n0 + 4 * qa, n0 + 4 * qb};
-    float cs[4], sn[4];
+  for (int q0 = slot; q0 < nquads; q0 += 4 * SL) {           // four quads = eight rotate-half pairs per batch of loads
+    int nq[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int c = 0; c < 4; ++c) nq[c] = n0 + 4 * min(q0 + c * SL, nquads - 1);
+    float cs[8], sn[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
       const int n = nq[u >> 1] + 2 * (u & 1);
       const int i = (n % dh) >> 1;                            // rotation angle index (unused for v heads)
       cs[u] = g.rope_cos[(size_t)rp.pos * half + i];
       sn[u] = g.rope_sin[(size_t)rp.pos * half + i];
     }
-    float val[8];
-    pt_sum8(g.PT, g.S, g.Npad, nq[0], nq[1], m, val);
+    float val[16];
+    pt_sum16(g.PT, g.S, g.Npad, nq[0], nq[1], nq[2], nq[3], m, val, val + 8);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if ((u >= 2 && q0 + SL >= nquads) || !live) continue;
+    for (int u = 0; u < 8; ++u) {
+      if (q0 + (u >> 1) * SL >= nquads || !live) continue;
       const int n = nq[u >> 1] + 2 * (u & 1), hd = n / dh, pr = n % dh;
       float a = val[2 * u] * rs, b = val[2 * u + 1] * rs;
       int d1, d2;
@@ -278,23 +291,44 @@ __device__ inline void epilogue_resid(const Gemm2& g, int grp, int n0, int n1, f
   }
 }
 
+__device__ inline void swiglu8(const float* gv, const float* uv, float rs, float* x) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float gg = gv[t] * rs, uu = uv[t] * rs;
+    x[t] = gg / (1.0f + __expf(-gg)) * uu;
+  }
+}
 template <int NXP>
 __device__ inline void epilogue_swiglu(const Gemm2& g, int n0, int n1, const float* rstd_s) {
   const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;
   const bool live = m < g.M;
   const float rs = live ? rstd_s[m] : 0.f;
-  const int items = ((n1 - n0) >> 5) * 2;
-  for (int it = slot; it < items; it += V2_THREADS / 32) {
+  const int items = ((n1 - n0) >> 5) * 2;                    // 8 outputs each: gate rows nb..nb+7, up rows 16 further
+  constexpr int SL = V2_THREADS / 32;
+  if (g.S <= 4) {
+    for (int it = slot; it < items; it += 2 * SL) {          // two items = 32 loads in flight
+      const int it2 = min(it + SL, items - 1);
+      const int nbA = n0 + (it >> 1) * 32 + 8 * (it & 1), nbB = n0 + (it2 >> 1) * 32 + 8 * (it2 & 1);
+      PtQuads4 qa, qb;
+      pt_issue16(qa, g.PT, g.S, g.Npad, nbA, nbA + 4, nbA + 16, nbA + 20, m);
+      pt_issue16(qb, g.PT, g.S, g.Npad, nbB, nbB + 4, nbB + 16, nbB + 20, m);
+      float x[8], gv[8], uv[8];
+      pt_finish16(qa, g.S, gv, uv);
+      swiglu8(gv, uv, rs, x);
+      if (live) xf_store8(g.xf_out, m, ((n0 >> 5) + (it >> 1)) * 16 + 8 * (it & 1), 1, g.xf_KS, NXP, x);
+      pt_finish16(qb, g.S, gv, uv);
+      swiglu8(gv, uv, rs, x);
+      if (live && it + SL < items) xf_store8(g.xf_out, m, ((n0 >> 5) + (it2 >> 1)) * 16 + 8 * (it2 & 1), 1, g.xf_KS, NXP, x);
+    }
+    return;
+  }
+  for (int it = slot; it < items; it += SL) {
     const int rb = it >> 1, c2 = it & 1;
-    const int nb = n0 + rb * 32 + 8 * c2;            // gate rows; the matching up rows are 16 further
+    const int nb = n0 + rb * 32 + 8 * c2;
     const int f = ((n0 >> 5) + rb) * 16 + 8 * c2;
     float x[8], gv[8], uv[8];
     pt_sum16(g.PT, g.S, g.Npad, nb, nb + 4, nb + 16, nb + 20, m, gv, uv);
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const float gg = gv[t] * rs, uu = uv[t] * rs;
-      x[t] = gg / (1.0f + __expf(-gg)) * uu;
-    }
+    swiglu8(gv, uv, rs, x);
     if (live) xf_store8(g.xf_out, m, f, 1, g.xf_KS, NXP, x);
   }
 }
@@ -627,6 +661,41 @@ __device__ inline void load8(const bf16_t* p, float* x) {
   x[6] = __builtin_bit_cast(float, r.w << 16); x[7] = __builtin_bit_cast(float, r.w & 0xFFFF0000u);
 }
 
+// Folds NS splits (e, e+1, ...) of one (row, head) into the running (max, denominator, CW outputs): every load of the
+// chunk is in flight before the first use.
+template <int DH, int CW, int NS>
+__device__ __forceinline__ void attn_merge_chunk(const float* part_o, const float* part_ml, size_t e0, int d0, float& mx, float& den, float* x) {
+  constexpr int NQ = CW / 4;
+  float msv[NS], lsv[NS];
+  f32x4 ov[NS][NQ];
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    const size_t e = e0 + u;
+    msv[u] = coh_load(part_ml + e * 2);
+    lsv[u] = coh_load(part_ml + e * 2 + 1);
+#pragma unroll
+    for (int qd = 0; qd < NQ; ++qd) ov[u][qd] = coh_load16(part_o, (uint32_t)((e * DH + d0 + 4 * qd) * 4));
+  }
+  float cmx = mx;
+#pragma unroll
+  for (int u = 0; u < NS; ++u) cmx = fmaxf(cmx, msv[u]);
+  const float resc = (mx == -INFINITY) ? 0.f : __expf(mx - cmx);   // nothing to rescale on the first chunk
+  den *= resc;
+#pragma unroll
+  for (int t = 0; t < CW; ++t) x[t] *= resc;
+  mx = cmx;
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    const float wv = (msv[u] != -INFINITY) ? __expf(msv[u] - mx) : 0.f;
+    den += wv * lsv[u];
+#pragma unroll
+    for (int qd = 0; qd < NQ; ++qd) {
+      x[4 * qd] += wv * ov[u][qd].x; x[4 * qd + 1] += wv * ov[u][qd].y;
+      x[4 * qd + 2] += wv * ov[u][qd].z; x[4 * qd + 3] += wv * ov[u][qd].w;
+    }
+  }
+}
+
 template <typename CT, int DH>
 __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
                                                const float* __restrict__ Q, float* part_o, float* part_ml, int H,
@@ -822,7 +891,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   // merge the splits of (sequence, head): thread = (row, CW-wide column chunk), one item per thread in the usual
   // shapes.  Every load of up to 8 splits -- (max, sum) pairs and partial outputs -- is in flight at once, so the
   // merge costs one memory round trip; more splits continue with a running rescale, in split order.
-  constexpr int CW = DH >= 128 ? 16 : 8, NQ = CW / 4;
+  constexpr int CW = DH >= 128 ? 16 : 8;
   for (int it = tid; it < R * (DH / CW); it += 256) {
     const int r = it / (DH / CW), d0 = (it % (DH / CW)) * CW;
     const size_t rowhead = ((size_t)(r0 + r) * H + hd) * n_splits;
@@ -830,33 +899,15 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
     for (int t = 0; t < CW; ++t) x[t] = 0.f;
     for (int sp0 = 0; sp0 < n_splits; sp0 += 8) {
-      float msv[8], lsv[8];
-      f32x4 ov[8][NQ];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const size_t e = rowhead + min(sp0 + u, n_splits - 1);
-        msv[u] = coh_load(part_ml + e * 2);
-        lsv[u] = coh_load(part_ml + e * 2 + 1);
-#pragma unroll
-        for (int qd = 0; qd < NQ; ++qd) ov[u][qd] = coh_load16(part_o, (uint32_t)((e * DH + d0 + 4 * qd) * 4));
-      }
-      float cmx = mx;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) if (sp0 + u < n_splits) cmx = fmaxf(cmx, msv[u]);
-      const float resc = (mx == -INFINITY) ? 0.f : __expf(mx - cmx);   // 1 on the first chunk's empty history
-      den *= resc;
-#pragma unroll
-      for (int t = 0; t < CW; ++t) x[t] *= resc;
-      mx = cmx;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float wv = (sp0 + u < n_splits && msv[u] != -INFINITY) ? __expf(msv[u] - mx) : 0.f;
-        den += wv * lsv[u];
-#pragma unroll
-        for (int qd = 0; qd < NQ; ++qd) {
-          x[4 * qd] += wv * ov[u][qd].x; x[4 * qd + 1] += wv * ov[u][qd].y;
-          x[4 * qd + 2] += wv * ov[u][qd].z; x[4 * qd + 3] += wv * ov[u][qd].w;
-        }
+      switch (min(n_splits - sp0, 8)) {                        // uniform: exactly the loads that are needed
+        case 1: attn_merge_chunk<DH, CW, 1>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 2: attn_merge_chunk<DH, CW, 2>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 3: attn_merge_chunk<DH, CW, 3>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 4: attn_merge_chunk<DH, CW, 4>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 5: attn_merge_chunk<DH, CW, 5>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 6: attn_merge_chunk<DH, CW, 6>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        case 7: attn_merge_chunk<DH, CW, 7>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
+        default: attn_merge_chunk<DH, CW, 8>(part_o, part_ml, rowhead + sp0, d0, mx, den, x); break;
       }
     }
     const float inv = den > 0.f ? 1.0f / den : 0.f;
