@@ -939,7 +939,8 @@ static int do_draft(eagle_ctx* c) {
   pass_ctx(c, p1);
   if ((rc = (D1 * B <= 32 ? head_forward2(c, p1, ctx, D1) : head_forward(c, p1, ctx + D1, D1, true)))) return rc;
   dim3 g0(1, B);
-  k_expand<<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
+  if (g.vocab > 32768) k_expand<true><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
+  else k_expand<false><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, getenv("EAGLE_EXPAND_TRACE") ? c->trace : nullptr);
   LAUNCH_CHECK();
   for (int lev = 1; lev < c->D; ++lev) {
     int nr = c->tree_h.n_level_rows[lev];
@@ -948,7 +949,8 @@ static int do_draft(eagle_ctx* c) {
     pass_ctx(c, pl);
     if ((rc = (nr * B <= 32 ? head_forward2(c, pl, ctx, c->M) : head_forward(c, pl, ctx + c->M, c->M, true)))) return rc;
     dim3 gl(nr, B);
-    k_expand<<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->gumbel);
+    if (g.vocab > 32768) k_expand<true><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
+    else k_expand<false><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
     LAUNCH_CHECK();
   }
   c->phase = 1;

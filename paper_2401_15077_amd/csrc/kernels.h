@@ -129,8 +129,18 @@ __device__ inline void block_argmax(float& v, int& i, float* shv, int* shi) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) { shv[w] = v; shi[w] = i; }
   __syncthreads();
-  v = shv[0]; i = shi[0];
-  for (int k = 1; k < nw; ++k) better(v, i, shv[k], shi[k]);
+  // second level: lanes 0..15 of every wave take one per-wave result each and reduce them with four exchanges (the
+  // (value, index) order is total, so the exchange pattern does not matter); lane 0 broadcasts
+  const int l = threadIdx.x & 63;
+  v = l < nw ? shv[l] : -INFINITY;
+  i = l < nw ? shi[l] : 0x7fffffff;
+  for (int o = 8; o > 0; o >>= 1) {
+    float v2 = __shfl_xor(v, o, 64);
+    int i2 = __shfl_xor(i, o, 64);
+    better(v, i, v2, i2);
+  }
+  v = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
+  i = __builtin_amdgcn_readfirstlane(i);
 }
 
 // ============================================================================ weight packing
@@ -623,87 +633,146 @@ struct HintDev {
 
 // Children of one tree node = the top-k entries of its (knob-adjusted, Gumbel-perturbed when non-greedy) head
 // logits, rank r = (r+1)-th largest, equal scores -> lower token id (App. A.1).  Block = (parent row, seq).
+template <bool BIGV>   // BIGV: more than 32768 vocabulary entries (the scores of a row do not fit the block's registers)
 __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_seq, const TreeDev* tree, SeqState st,
                                                  float* draft_logits /*[seq][M][V]*/, int* tree_tok, int* on_path, HintDev hint,
-                                                 int V, float temperature, unsigned long long rng_seed, float* scratch /*[seq][rows][V]*/) {
+                                                 int V, float temperature, unsigned long long rng_seed, unsigned long long* trace) {
   __shared__ float shv[16];
   __shared__ int shi[16];
   const int seq = blockIdx.y;
+  unsigned long long* tr = (trace && threadIdx.x == 0 && blockIdx.x == 0 && seq == 0) ? trace : nullptr;
+  if (tr) tr[0] = wall_clock64();
   const int v = level < 0 ? 0 : tree->level_rows[level][blockIdx.x];
   const int M = tree->M;
   float* lg = draft_logits + ((size_t)seq * M + v) * V;
+  // Loads are grouped by what they depend on, so that the kernel pays two memory round trips, not one per fact:
+  // (1) everything addressed by (seq, v) alone, including the first 32 logits of every thread ...
+  constexpr int XPT = 32;                                      // logits per thread and chunk (1024 threads: 32768)
+  float x[XPT];
+#pragma unroll
+  for (int u = 0; u < XPT; ++u) x[u] = lg[min(u * 1024 + (int)threadIdx.x, V - 1)];
   const int n = st.n_tok[seq];
-  if (v == 0 && threadIdx.x == 0) {
-    tree_tok[seq * M] = st.tokens[(size_t)seq * st.tok_stride + n - 1];
-    int hn = hint.n[seq];
-    on_path[seq * M] = (hn > n - 1) && hint.future[(size_t)seq * hint.stride + n - 1] == tree_tok[seq * M];
+  const int hn = hint.n[seq];
+  const unsigned long long hseed = hint.seed[seq];
+  const float halpha = hint.alpha[seq], hbias = hint.bias[seq];
+  const int depth_v = tree->depth[v], nk = tree->nchild[v];
+  const int on_v = v == 0 ? 0 : on_path[seq * M + v];
+  const unsigned long long step_no = (unsigned long long)st.step_no[seq];
+  // (2) ... then what needs the sequence length: the root token, the target's future tokens at two positions
+  const int stride = hint.stride;
+  const int pos_child = n + depth_v;
+  const int root_tok = st.tokens[(size_t)seq * st.tok_stride + max(n - 1, 0)];
+  const int fut_root = hint.future[(size_t)seq * stride + min(max(n - 1, 0), stride - 1)];
+  const int fut_child = hint.future[(size_t)seq * stride + min(pos_child, stride - 1)];
+  int on = on_v;
+  if (v == 0) {
+    on = (hn > n - 1) && fut_root == root_tok;
+    if (threadIdx.x == 0) { tree_tok[seq * M] = root_tok; on_path[seq * M] = on; }
   }
-  __syncthreads();
   // acceptance knob of the synthetic workload
-  const int pos_child = n + tree->depth[v];
-  int hinted = -1;
-  if (on_path[seq * M + v] && pos_child < hint.n[seq]) {
-    hinted = hint.future[(size_t)seq * hint.stride + pos_child];
-  }
-  const int nk = tree->nchild[v];
-  // One pass over the logits: every thread keeps the best nk of its own entries (sorted, ties to the lower token id),
-  // then nk block-wide rounds pick the overall best among the threads' current heads.  The knob's bias is applied on
-  // the fly (and written back by the thread that owns the hinted token, since later phases read the adjusted logits).
+  const int hinted = (on && pos_child < hn) ? fut_child : -1;
   float adj = 0.f;
   if (hinted >= 0) {
-    uint32_t k24 = rng_u24(rng_prefix(hint.seed[seq], PURPOSE_HINT, 0), (uint32_t)seq, 0, (uint32_t)pos_child);
-    adj = ((float)k24 * 5.9604644775390625e-8f < hint.alpha[seq]) ? hint.bias[seq] : -hint.bias[seq];
+    uint32_t k24 = rng_u24(rng_prefix(hseed, PURPOSE_HINT, 0), (uint32_t)seq, 0, (uint32_t)pos_child);
+    adj = ((float)k24 * 5.9604644775390625e-8f < halpha) ? hbias : -hbias;
   }
   const bool gumbel = temperature > 0.f;
   unsigned long long pre = 0ull;
-  if (gumbel) pre = rng_prefix(rng_seed, PURPOSE_GUMBEL, (unsigned long long)st.step_no[seq]);
-  float tv[EAGLE_MAX_CHILD];
-  int ti[EAGLE_MAX_CHILD];
+  if (gumbel) pre = rng_prefix(rng_seed, PURPOSE_GUMBEL, step_no);
+  int childs[EAGLE_MAX_CHILD];
 #pragma unroll
-  for (int q = 0; q < EAGLE_MAX_CHILD; ++q) { tv[q] = -INFINITY; ti[q] = 0x7fffffff; }
-  for (int j0 = 0; j0 < V; j0 += 8 * 1024) {                 // 8 entries per thread in flight
-    float x[8];
+  for (int q = 0; q < EAGLE_MAX_CHILD; ++q) childs[q] = tree->child[v][q];
+  int picked[EAGLE_MAX_CHILD];                                 // thread 0 writes the results once, after the rounds
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + u * 1024 + (int)threadIdx.x;
-      x[u] = lg[min(j, V - 1)];
-    }
+  for (int q = 0; q < EAGLE_MAX_CHILD; ++q) picked[q] = 0;
+  if (tr) tr[1] = wall_clock64() + (x[0] == 12345.f ? 1 : 0);
+  if constexpr (!BIGV) {
+    // Scores stay in registers.  Every thread offers its best entry; the block picks the overall best (ties to the
+    // lower token id); only the thread that owned it removes it and looks for its next best.
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + u * 1024 + (int)threadIdx.x;
-      if (j >= V) continue;
+    for (int u = 0; u < XPT; ++u) {
+      const int j = u * 1024 + (int)threadIdx.x;
       float sc = x[u];
-      if (j == hinted) { sc += adj; lg[j] = sc; }
+      if (j == hinted) { sc += adj; lg[j] = sc; }            // later phases read the adjusted logits
       if (gumbel) {
-        float un = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)j) + 0.5f) * 5.9604644775390625e-8f;
+        float un = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)min(j, V - 1)) + 0.5f) * 5.9604644775390625e-8f;
         sc = sc / temperature - logf(-logf(un));
       }
-      // insert (sc, j) into the sorted list
-      float cv = sc; int ci = j;
+      x[u] = j < V ? sc : -INFINITY;
+    }
+    float lv = -INFINITY; int li = 0x7fffffff;
 #pragma unroll
-      for (int q = 0; q < EAGLE_MAX_CHILD; ++q) {
-        const bool win = cv > tv[q] || (cv == tv[q] && ci < ti[q]);
-        const float ov = tv[q]; const int oi = ti[q];
-        if (win) { tv[q] = cv; ti[q] = ci; cv = ov; ci = oi; }
+    for (int u = 0; u < XPT; ++u) better(lv, li, x[u], u * 1024 + (int)threadIdx.x);
+    if (tr) tr[2] = wall_clock64() + (lv == 12345.f ? 1 : 0);
+    for (int r = 0; r < nk; ++r) {
+      float bv = lv; int bi = li;
+      block_argmax(bv, bi, shv, shi);
+      if (bi == li) {                                           // mine: take it out, find my next best
+        lv = -INFINITY; li = 0x7fffffff;
+#pragma unroll
+        for (int u = 0; u < XPT; ++u) {
+          const int j = u * 1024 + (int)threadIdx.x;
+          if (j == bi) x[u] = -INFINITY;
+          better(lv, li, x[u], j);
+        }
+        if (lv == -INFINITY) li = 0x7fffffff;
+      }
+#pragma unroll
+      for (int q = 0; q < EAGLE_MAX_CHILD; ++q) if (q == r) picked[q] = bi;
+      __syncthreads();                                          // shv / shi are reused by the next round
+    }
+  } else {
+    // Larger vocabularies: one pass with a per-thread sorted top-nk list, then rounds over the lists' heads.
+    float tv[EAGLE_MAX_CHILD];
+    int ti[EAGLE_MAX_CHILD];
+#pragma unroll
+    for (int q = 0; q < EAGLE_MAX_CHILD; ++q) { tv[q] = -INFINITY; ti[q] = 0x7fffffff; }
+    for (int j0 = 0; j0 < V; j0 += XPT * 1024) {
+      if (j0 > 0) {
+#pragma unroll
+        for (int u = 0; u < XPT; ++u) x[u] = lg[min(j0 + u * 1024 + (int)threadIdx.x, V - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < XPT; ++u) {
+        const int j = j0 + u * 1024 + (int)threadIdx.x;
+        if (j >= V) continue;
+        float sc = x[u];
+        if (j == hinted) { sc += adj; lg[j] = sc; }
+        if (gumbel) {
+          float un = ((float)rng_u24(pre, (uint32_t)seq, (uint32_t)v, (uint32_t)j) + 0.5f) * 5.9604644775390625e-8f;
+          sc = sc / temperature - logf(-logf(un));
+        }
+        float cv = sc; int ci = j;
+#pragma unroll
+        for (int q = 0; q < EAGLE_MAX_CHILD; ++q) {
+          const bool win = cv > tv[q] || (cv == tv[q] && ci < ti[q]);
+          const float ov = tv[q]; const int oi = ti[q];
+          if (win) { tv[q] = cv; ti[q] = ci; cv = ov; ci = oi; }
+        }
       }
     }
-  }
-  for (int r = 0; r < nk; ++r) {
-    float bv = tv[0];
-    int bi = ti[0];
-    block_argmax(bv, bi, shv, shi);
-    if (bi == ti[0]) {                                          // this thread's head won: advance its list
+    for (int r = 0; r < nk; ++r) {
+      float bv = tv[0]; int bi = ti[0];
+      block_argmax(bv, bi, shv, shi);
+      if (bi == ti[0]) {
 #pragma unroll
-      for (int q = 0; q + 1 < EAGLE_MAX_CHILD; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
-      tv[EAGLE_MAX_CHILD - 1] = -INFINITY; ti[EAGLE_MAX_CHILD - 1] = 0x7fffffff;
+        for (int q = 0; q + 1 < EAGLE_MAX_CHILD; ++q) { tv[q] = tv[q + 1]; ti[q] = ti[q + 1]; }
+        tv[EAGLE_MAX_CHILD - 1] = -INFINITY; ti[EAGLE_MAX_CHILD - 1] = 0x7fffffff;
+      }
+#pragma unroll
+      for (int q = 0; q < EAGLE_MAX_CHILD; ++q) if (q == r) picked[q] = bi;
+      __syncthreads();
     }
-    if (threadIdx.x == 0) {
-      int c = tree->child[v][r];
-      tree_tok[seq * M + c] = bi;
-      on_path[seq * M + c] = (hinted >= 0 && bi == hinted);
-    }
-    __syncthreads();
   }
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int q = 0; q < EAGLE_MAX_CHILD; ++q)
+      if (q < nk) {
+        tree_tok[seq * M + childs[q]] = picked[q];
+        on_path[seq * M + childs[q]] = (hinted >= 0 && picked[q] == hinted);
+      }
+  }
+  if (tr) tr[3] = wall_clock64();
 }
 
 // softmax(x / T) over V entries into p (block-wide), returns nothing; sh >= 16 floats
