@@ -149,6 +149,8 @@ typedef struct {
   int64_t steps;
   double gemm_ms; int64_t gemm_launches; double gemm_weight_bytes;  /* mode 2 only */
   double verify_weight_bytes, verify_kv_bytes;                    /* algorithmic bytes of the verify phases */
+  double event_pair_ms;   /* mode 2: what two consecutive event records measure with nothing between them (each GEMM
+                             launch in gemm_ms carries this much on top of the kernel's own duration) */
 } eagle_profile;
 int eagle_get_profile(eagle_ctx *ctx, eagle_profile *out, int32_t reset);
 

@@ -47,7 +47,7 @@ class EagleProfile(ctypes.Structure):
     _fields_ = [("draft_ms", ctypes.c_double), ("verify_ms", ctypes.c_double), ("accept_ms", ctypes.c_double),
                 ("steps", ctypes.c_int64), ("gemm_ms", ctypes.c_double), ("gemm_launches", ctypes.c_int64),
                 ("gemm_weight_bytes", ctypes.c_double), ("verify_weight_bytes", ctypes.c_double),
-                ("verify_kv_bytes", ctypes.c_double)]
+                ("verify_kv_bytes", ctypes.c_double), ("event_pair_ms", ctypes.c_double)]
 
 
 class EagleError(RuntimeError):

@@ -94,6 +94,7 @@ struct eagle_ctx {
   hipEvent_t ev[4];
   std::vector<hipEvent_t> gemm_ev; size_t gemm_ev_used = 0; std::vector<double> gemm_ev_bytes;
   eagle_profile prof;
+  double event_pair_ms = 0;
 };
 
 static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
@@ -1162,11 +1163,24 @@ extern "C" int eagle_get_kv_row(eagle_ctx* c, int32_t seq, int32_t layer, int32_
 extern "C" int eagle_set_profiling(eagle_ctx* c, int32_t mode) {
   if (!c || mode < 0 || mode > 2) return fail(EAGLE_EINVAL, "mode must be 0, 1 or 2");
   c->prof_mode = mode;
+  if (mode == 2) {
+    // what a pair of events costs with nothing between them: subtracted by callers that want the kernel's own time
+    const int n = 64;
+    if (c->gemm_ev.size() < (size_t)n + 1)
+      for (int i = (int)c->gemm_ev.size(); i < n + 1; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
+    HIPCHK(hipStreamSynchronize(c->stream));
+    for (int i = 0; i <= n; ++i) HIPCHK(hipEventRecord(c->gemm_ev[i], c->stream));
+    HIPCHK(hipStreamSynchronize(c->stream));
+    double tot = 0;
+    for (int i = 0; i < n; ++i) { float ms = 0.f; HIPCHK(hipEventElapsedTime(&ms, c->gemm_ev[i], c->gemm_ev[i + 1])); tot += ms; }
+    c->event_pair_ms = tot / n;
+  }
   return EAGLE_OK;
 }
 extern "C" int eagle_get_profile(eagle_ctx* c, eagle_profile* out, int32_t reset) {
   if (!c || !out) return fail(EAGLE_EINVAL, "null argument");
   *out = c->prof;
+  out->event_pair_ms = c->event_pair_ms;
   if (reset) memset(&c->prof, 0, sizeof(c->prof));
   return EAGLE_OK;
 }
