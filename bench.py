@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--tau", type=float, default=3.5)
     ap.add_argument("--tree", default="T26")
     ap.add_argument("--seed", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (each with its own prompt and knob)")
+    ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic tree acceptance, no knob (natural acceptance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=3)
     ap.add_argument("--cpu-prompt", type=int, default=48)
@@ -73,27 +75,36 @@ def main() -> int:
     D = max(depth)
     n_future = (K + W + 2) * (D + 1) + 8
     max_seq = args.prompt + n_future + M + 16
+    B = args.batch
+    stochastic = args.temperature > 0.0
     t0 = time.time()
-    eng = pkg.Eagle(shape, par, rk, max_batch=1, max_seq=max_seq)
+    eng = pkg.Eagle(shape, par, rk, max_batch=B, max_seq=max_seq, temperature=args.temperature, seed=args.seed)
     eng.load_weights(synth.iter_weights(shape, args.seed, synth.device_fmt(shape)))
     t_load = time.time() - t0
-    prompt = synth.prompt(args.seed, args.prompt, shape.vocab)
+    prompts = [synth.prompt(args.seed + 1000 * b, args.prompt, shape.vocab) for b in range(B)]
+    prompt = prompts[0]
 
-    # the target's own greedy continuation (vanilla decoding with the same kernels), outside the timed region
-    first = eng.prefill(0, prompt)
-    future = list(prompt) + [first]
+    # the target's own continuation (vanilla decoding with the same kernels), outside the timed region: the knob's
+    # hints when greedy, and the vanilla tokens/s in any case
+    futures = [list(prompts[b]) + [eng.prefill(b, prompts[b])] for b in range(B)]
+    torch.cuda.synchronize()
     tv0 = time.time()
     for _ in range(n_future):
-        future.append(int(eng.vanilla_step()[0]))
+        tk = eng.vanilla_step()
+        for b in range(B):
+            futures[b].append(int(tk[b]))
     torch.cuda.synchronize()
-    vanilla_tok_s = n_future / (time.time() - tv0)
+    vanilla_tok_s = n_future * B / (time.time() - tv0)
+    future = futures[0]
     alpha = solve_alpha(args.tau, D)
     hint_seed = 20240126
 
     def run(mode: int, steps: int):
         eng.reset()
-        eng.prefill(0, prompt)
-        eng.set_hint(0, future, alpha, HINT_BIAS, hint_seed)
+        for b in range(B):
+            eng.prefill(b, prompts[b])
+            if not stochastic:
+                eng.set_hint(b, futures[b], alpha, HINT_BIAS, hint_seed + b)
         eng.set_profiling(0)
         for _ in range(W):
             eng.step()
@@ -104,7 +115,7 @@ def main() -> int:
         emitted = 0
         for _ in range(steps):
             _, lens, _ = eng.step()
-            emitted += int(lens[0])
+            emitted += int(lens.sum())
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
         prof = eng.get_profile(reset=True)
@@ -112,8 +123,11 @@ def main() -> int:
         return dt, emitted, prof
 
     dt, emitted, _ = run(0, K)                       # the timed region: exactly K steps
-    toks = eng.get_buffer(pkg.BUF_TOKENS)
-    stale = not np.array_equal(toks, np.asarray(future[:len(toks)], np.int32))
+    stale = False
+    if not stochastic:
+        for b in range(B):
+            toks = eng.get_buffer(pkg.BUF_TOKENS, b)
+            stale = stale or not np.array_equal(toks, np.asarray(futures[b][:len(toks)], np.int32))
     _, _, prof1 = run(1, K)                          # same K steps with phase events
     _, _, prof2 = run(2, min(K, 16))                 # per-launch events around the GEMM kernel
 
@@ -128,17 +142,19 @@ def main() -> int:
     gemm_gbs = prof2["gemm_weight_bytes"] / (gemm_ms * 1e-3) / 1e9
     # HBM bytes per launch of the same kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (each scaled by what the
     # counter reads for a copy of known size), measured on this workload; only quoted for this workload
-    default_workload = (args.shape == "llama2-7b" and not args.layers and args.tree == "T26" and args.prompt == 512)
+    default_workload = (args.shape == "llama2-7b" and not args.layers and args.tree == "T26" and args.prompt == 512
+                        and B == 1 and not stochastic)
     traffic = 113.8e6 + 6.8e6 if default_workload else None
     out = {
         "metric": "decode tokens/s + verify-step ms, LLaMA2-7B shape bs=1; % HBM roofline",
         "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{shape.name} bs=1 prompt={args.prompt} tree={args.tree}({M} nodes, depth {D}) greedy "
-                               f"knob alpha={alpha:.4f}", "global_batch": 1, "seq_len": args.prompt,
+        "config": {"workload": f"{shape.name} bs={B} prompt={args.prompt} tree={args.tree}({M} nodes, depth {D}) "
+                               + (f"temperature {args.temperature} (Alg. 1), no knob" if stochastic else f"greedy knob alpha={alpha:.4f}"),
+                   "global_batch": B, "seq_len": args.prompt,
                    "n_layers": shape.n_layers},
-        "tau": emitted / K, "verify_ms": verify_ms, "draft_ms": draft_ms, "accept_ms": accept_ms,
+        "tau": emitted / K / B, "verify_ms": verify_ms, "draft_ms": draft_ms, "accept_ms": accept_ms,
         "verify_hbm_frac": verify_bytes / (verify_ms * 1e-3) / 8e12 if verify_ms > 0 else None,
         "verify_bytes": verify_bytes, "vanilla_tokens_per_s": vanilla_tok_s, "hint_stale": bool(stale),
         "load_s": t_load,
@@ -153,7 +169,7 @@ def main() -> int:
     del eng
     torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and B == 1 and not stochastic:
         from oracle.eagle_oracle import Oracle
         cp = args.cpu_prompt
         Wo = synth.make_weights(shape, args.seed, synth.oracle_fmt(shape))

@@ -961,10 +961,25 @@ static int do_draft(eagle_ctx* c) {
 static int do_verify(eagle_ctx* c) {
   if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
   c->gemm_no = 0; c->attn_no = 0;
-  Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
-  pass_ctx(c, pv);
-  int rc = c->M * c->n_active <= 32 ? target_forward2(c, pv, max_ctx(c), c->M, c->L, 0)
-                                    : target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
+  int rc = EAGLE_OK;
+  if (c->M * c->n_active <= 32) {
+    Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
+    pass_ctx(c, pv);
+    rc = target_forward2(c, pv, max_ctx(c), c->M, c->L, 0);
+  } else if (c->M <= 32) {
+    // Several sequences whose trees do not fit one 32-row pass together: one fast-path pass per sequence.  The
+    // weights are streamed once per sequence, which is still quicker than the 128-row general path on this machine
+    // (measured at the 7B shape, 4 x 26 rows: 20 ms against 33 ms).
+    for (int s = 0; s < c->n_active && !rc; ++s) {
+      Pass pv{PASS_VERIFY, c->M, 1, s, 0, 0, 0};
+      pass_ctx(c, pv);
+      rc = target_forward2(c, pv, c->h_ctx[s], c->M, c->L, 0);
+    }
+  } else {
+    Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
+    pass_ctx(c, pv);
+    rc = target_forward(c, pv, max_ctx(c) + c->M, c->M, true, c->L, 0, 0);
+  }
   if (rc) return rc;
   c->phase = 2;
   return EAGLE_OK;

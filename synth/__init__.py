@@ -187,11 +187,21 @@ def tree_from_paths(paths: List[str]) -> Tuple[np.ndarray, np.ndarray]:
     return np.asarray(parent, np.int32), np.asarray(rank, np.int32)
 
 
+def _full_binary(depth: int) -> List[str]:
+    out, level = [], [""]
+    for _ in range(depth):
+        level = [p + c for p in level for c in "01"]
+        out += level
+    return out
+
+
 TREES: Dict[str, Tuple[np.ndarray, np.ndarray]] = {
     "T26": tree_from_paths(_T26),
     "T15": tree_from_paths(_T15),
     "T10": tree_from_paths(_T10),
     "chain5": tree_from_paths(_CHAIN5),
+    "root": tree_from_paths([]),             # degenerate: no drafts at all, a step is one vanilla step
+    "B63": tree_from_paths(_full_binary(5)),  # full binary tree of depth 5: 63 nodes (more rows than one 32-row pass)
 }
 
 
@@ -214,16 +224,23 @@ def _layer_specs(s: ModelShape, moe: bool) -> List[Tuple[str, Tuple[int, ...], f
 
 def tensor_specs(s: ModelShape) -> List[Tuple[str, int, Tuple[int, ...], float, float]]:
     """All tensors of target + EAGLE head: (name, tid, shape, std, mean).
-    Matrices are row-major [out_features, in_features]; norm gains ~ N(1, 0.02); FC bias ~ N(0, 0.02)."""
+    Matrices are row-major [out_features, in_features], N(0, 0.02) except the head's FC; norm gains ~ N(1, 0.02);
+    FC bias ~ N(0, 0.02)."""
     specs = [("embed", 1, (s.vocab, s.d_model), 0.02, 0.0),
              ("lm_head", 2, (s.vocab, s.d_model), 0.02, 0.0),
              ("final_norm", 3, (s.d_model,), 0.02, 1.0),
-             ("head.fc_w", 4, (s.d_model, 2 * s.d_model), 0.02, 0.0),
+             # std (2d)^-1/2: the FC output keeps the scale of its input, as a trained head's features keep the scale of
+             # the target's; with 0.02 the head's feature norm grows 1.8-2.6x per tree level (fan-in 2d)
+             ("head.fc_w", 4, (s.d_model, 2 * s.d_model), (2 * s.d_model) ** -0.5, 0.0),
              ("head.fc_b", 5, (s.d_model,), 0.02, 0.0)]
     for li in range(s.n_layers):
         for k, (nm, shp, std, mean) in enumerate(_layer_specs(s, s.n_experts > 0)):
             specs.append((f"layers.{li}.{nm}", 1024 + li * 16 + _LAYER_FIELDS.index(nm), shp, std, mean))
     for nm, shp, std, mean in _layer_specs(s, s.n_experts > 0 and s.draft_moe):
+        # the head has no final norm, so its residual branches are scaled down (output projections with gain 1/4):
+        # f-hat then has the scale of the target's normalised feature, which is what a trained head regresses to
+        if nm in ("wo", "down"):
+            std = 0.25 * shp[-1] ** -0.5
         specs.append((f"head.layer.{nm}", 512 + _LAYER_FIELDS.index(nm), shp, std, mean))
     return specs
 

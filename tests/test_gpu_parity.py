@@ -155,8 +155,8 @@ def test_moe_twin_bf16_lockstep():
 
 
 def test_batch4_lockstep():
-    """Four independent sequences (different prompts) advance together: rows of all slots share the GEMMs
-    (verify has 4 x 15 = 60 rows and takes the general path, the head's tree levels take the fast path)."""
+    """Four independent sequences (different prompt lengths) advance together: the head's passes put the rows of all
+    slots through the same GEMMs; the 4 x 15 verify rows exceed one 32-row pass and are verified slot by slot."""
     s = synth.SHAPES["tiny"]
     par, rk = synth.TREES["T15"]
     eng = pkg.Eagle(s, par, rk, max_batch=4, max_seq=160)
@@ -195,3 +195,62 @@ def test_llama7b_full_depth_lockstep():
     st, toks, future = run_twin("llama2-7b", "T26", seed=2, n_layers=32, prompt_len=48, n_new=12, alpha=0.7773, max_seq=256)
     assert toks[:60] == future[:60]
     assert st.max_logit_err < 2e-2 and st.max_feat_err < 2e-2
+
+
+
+def test_llama13b_twin_bf16_lockstep():
+    """LLaMA2-13B widths (d 5120, 40 x 128 heads, FFN 13824): K slices that are not powers of two (5 and 14)."""
+    st, toks, future = run_twin("llama2-13b", "T26", seed=3, n_layers=2, prompt_len=72, n_new=24, alpha=0.7773)
+    assert toks[:72 + 24] == future[:72 + 24]
+
+
+def test_llama70b_twin_bf16_lockstep():
+    """LLaMA2-70B widths (d 8192, 64 query heads on 8 KV heads, FFN 28672), 2 target layers: 28 K slices in the down
+    projection, more work-groups than CUs in gate/up, grouped-query attention at head_dim 128."""
+    st, toks, future = run_twin("llama2-70b", "T26", seed=4, n_layers=2, prompt_len=40, n_new=12, alpha=0.7773, max_seq=256)
+    assert toks[:52] == future[:52]
+
+
+@pytest.mark.parametrize("tree,n_new", [("root", 10), ("chain5", 24), ("B63", 24)])
+def test_tiny_other_trees(tree, n_new):
+    """Degenerate and large trees on the tiny fp32 model: a tree of the root alone (every step is a vanilla step and
+    emits exactly one token), a chain, and a 63-node full binary tree (verify rows exceed one 32-row pass: the
+    128-row general path; its deepest level has 32 rows)."""
+    s, eng, orc = make_pair("tiny", tree, seed=9)
+    prompt = synth.prompt(9, 20, s.vocab)
+    check_prefill(eng, orc, prompt, TOL["fp32"])
+    st = Stats()
+    while len(orc.x) < len(prompt) + n_new:
+        lockstep_step(eng, orc, st, TOL["fp32"])
+    assert st.excused_accepts == 0 and st.excused_tree_slots == 0
+    assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x
+    if tree == "root":
+        assert all(n == 1 for n in st.lens)
+    van = Oracle(s, synth.make_weights(s, 9, synth.oracle_fmt(s)), *synth.TREES[tree], max_seq=256).generate_vanilla(prompt, n_new)
+    assert orc.x[len(prompt):len(prompt) + n_new] == van[:n_new]
+    eng.close()
+
+
+def test_tiny_edges_one_token_prompt_page_crossing_and_full_cache():
+    """A one-token prompt; decoding across KV page boundaries (64-token pages: positions 63/64 and 127/128 are
+    crossed by tree slots and by compaction); and the error when the cache cannot hold another tree."""
+    s, eng, orc = make_pair("tiny", "T15", seed=11, max_seq=160)
+    prompt = synth.prompt(11, 1, s.vocab)
+    check_prefill(eng, orc, prompt, TOL["fp32"])
+    st = Stats()
+    with pytest.raises(pkg.EagleError) as err:
+        while True:
+            if orc.ctx + orc.tree.M + 1 > 160:
+                eng.step()                      # must refuse: the tree no longer fits
+                break
+            lockstep_step(eng, orc, st, TOL["fp32"])
+    assert err.value.code == -3                 # EAGLE_ESEQ_FULL
+    assert orc.ctx > 128 and st.excused_accepts == 0
+    assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x
+    # KV rows on both sides of the page boundaries equal the oracle's
+    for layer in range(s.n_layers):
+        for pos in (0, 63, 64, 65, 127, 128, orc.ctx - 1):
+            k, v = eng.get_kv_row(0, layer, pos)
+            assert np.abs(k - orc.kc[layer][pos].reshape(-1)).max() < 1e-4
+            assert np.abs(v - orc.vc[layer][pos].reshape(-1)).max() < 1e-4
+    eng.close()
