@@ -81,7 +81,7 @@ struct eagle_ctx {
   // fast path (passes of <= 32 rows)
   float *h2, *PT2, *ssq1, *ssq2; int *cnt_gemm, *cnt_attn; size_t pt2_floats;
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
-  float *moe_w, *xn; int* expert_used;    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
+  float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
   int n_cu = 256;
@@ -292,6 +292,7 @@ static size_t layout(eagle_ctx* c) {
   c->xf2_dB = a.take<bf16_t>(g.n_experts > 0 ? (size_t)c->NXP * 32 * d : 8);
   c->moe_w = a.take<float>((size_t)std::max(1, g.n_experts) * 128);
   c->expert_used = a.take<int>(std::max(1, g.n_experts));
+  c->experts_touched = a.take<int>(1);
   c->xn = a.take<float>(g.n_experts > 0 ? (size_t)Mm * d : 8);
   c->xf2_2d = a.take<bf16_t>((size_t)c->NXP * 32 * 2 * d);
   c->xf2_att = a.take<bf16_t>((size_t)c->NXP * 32 * H * dh);
@@ -593,6 +594,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     LAUNCH_CHECK();
     k_router<<<M, 256, 0, c->stream>>>(c->xn, nullptr, nullptr, 0, 0.f, 0.f, nullptr, w.router, E, g.experts_per_tok, g.d_model, M, c->moe_w, 128, c->expert_used);
     LAUNCH_CHECK();
+    if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
       if ((rc = gemm(c, w.e_gu[e], c->xf_d, MT, &S))) return rc;
       dim3 grid((F / 8 + 255) / 256, M);
@@ -771,6 +773,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
     k_router<<<M, 256, 0, c->stream>>>(nullptr, c->h2, c->ssq1, c->ssq1_groups, 1.0f / (float)d, cf.rms_eps, w.mlp_norm, w.router, E,
                                        cf.experts_per_tok, d, M, c->moe_w, 128, c->expert_used);
     LAUNCH_CHECK();
+    if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
       g = gemm2_base(c, pass, M);
       g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
@@ -962,6 +965,7 @@ static int do_verify(eagle_ctx* c) {
   if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_verify needs a drafted tree (call eagle_draft_tree first)");
   c->gemm_no = 0; c->attn_no = 0;
   int rc = EAGLE_OK;
+  if (c->prof_mode && c->cfg.n_experts > 0) { k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->experts_touched, 0u, 1); LAUNCH_CHECK(); }
   if (c->M * c->n_active <= 32) {
     Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
     pass_ctx(c, pv);
@@ -1062,6 +1066,13 @@ extern "C" int eagle_step(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, i
       const LayerW& w = c->layers[l];
       wbytes += ((double)w.qkv.N * w.qkv.K + (double)w.o.N * w.o.K) * c->elt;
       if (!w.moe) wbytes += ((double)w.gu.N * w.gu.K + (double)w.dn.N * w.dn.K) * c->elt;
+    }
+    if (g.n_experts > 0) {   // experts that at least one row selected, summed over the layers (counted on the device)
+      int touched = 0;
+      HIPCHK(hipMemcpy(&touched, c->experts_touched, 4, hipMemcpyDeviceToHost));
+      const LayerW& w = c->layers[0];
+      wbytes += (double)touched * ((double)w.e_gu[0].N * w.e_gu[0].K + (double)w.e_dn[0].N * w.e_dn[0].K) * c->elt
+                + (double)g.n_layers * g.n_experts * g.d_model * 4.0;
     }
     double kvb = 0;
     for (int s = 0; s < c->n_active; ++s)   // context read once + the tree's own rows written

@@ -1052,6 +1052,15 @@ __global__ void k_read_kv_row(KVCache kv, int seq, int pos, float* kout, float* 
   }
 }
 
+// Profiling: adds the number of experts at least one row selected (flags set by k_router) to a running total.
+__global__ void k_count_used(const int* expert_used, int E, int* total) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int n = 0;
+    for (int e = 0; e < E; ++e) n += expert_used[e] != 0;
+    *total += n;
+  }
+}
+
 __global__ void k_fill_u32(uint32_t* p, uint32_t v, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
