@@ -44,7 +44,7 @@ __host__ __device__ inline size_t wpack_index(int n, int k, int KS) {
 __host__ __device__ inline size_t xf_index(int m, int k, int plane, int MT, int KS) {
   return (((size_t)plane * MT + (m >> 5)) * KS + (k >> 4)) * 512 + (size_t)((m & 31) + 32 * ((k & 15) >> 3)) * 8 + (k & 7);
 }
-// Split-K partial sums, transposed: PT[s][n][m], m fastest, Mpad = 32*MT floats per n.
+// Split-K partial sums of the general path: PT[s][m][n], n fastest (Mpad = 32*MT rows of Npad floats per split).
 
 // ---------------------------------------------------------------- counter-based uniforms (24-bit)
 #define EAGLE_GOLDEN 0x9E3779B97F4A7C15ull

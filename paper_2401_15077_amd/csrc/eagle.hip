@@ -299,7 +299,7 @@ static size_t layout(eagle_ctx* c) {
   c->xf2_ffn = a.take<bf16_t>((size_t)c->NXP * 32 * F);
   c->ssq1 = a.take<float>(256 * 32); c->ssq2 = a.take<float>(256 * 32);
   c->trace = a.take<unsigned long long>(1024 * 8);
-  c->cnt_gemm = a.take<int>(1024); c->cnt_attn = a.take<int>((size_t)64 * H);
+  c->cnt_gemm = a.take<int>(1024); c->cnt_attn = a.take<int>((size_t)128 * H);
   size_t worst2 = 0;
   auto consider2 = [&](const PackedW& w) {
     Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
@@ -572,16 +572,21 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     LAUNCH_CHECK();
   }
   {
-    int n_splits = std::max(1, std::min(16, (t_max + 63) / 64));
+    // the MFMA attention kernel of the fast path, one work-group per (KV split, head, sequence x 32-row block)
+    int n_splits = std::max(1, std::min(16, (t_max + 127) / 128));
     int rblocks = (pass.rows_per_seq + 31) / 32;
+    if (pass.n_seq * rblocks > 128) return fail(EAGLE_EINVAL, "internal: too many (sequence, row block) pairs in one pass");
     dim3 grid(n_splits, H, pass.n_seq * rblocks);
     float scale = 1.0f / std::sqrt((float)dh);
-#define ATTN(CT, DH) k_attn<CT, DH><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale)
-    if (c->kv_f32) { if (dh == 128) ATTN(float, 128); else if (dh == 64) ATTN(float, 64); else ATTN(float, 32); }
-    else { if (dh == 128) ATTN(bf16_t, 128); else if (dh == 64) ATTN(bf16_t, 64); else ATTN(bf16_t, 32); }
-#undef ATTN
-    LAUNCH_CHECK();
-    k_attn_combine<<<M, 256, 0, c->stream>>>(c->part_o, c->part_ml, H, dh, n_splits, c->xf_att, MT, c->NXP);
+#define ATTNG(CT, DH)                                                                                                   \
+  do {                                                                                                                  \
+    HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   \
+    k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
+        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf_att, c->NXP, nullptr, MT, rblocks); \
+  } while (0)
+    if (c->kv_f32) { if (dh == 128) ATTNG(float, 128); else if (dh == 64) ATTNG(float, 64); else ATTNG(float, 32); }
+    else { if (dh == 128) ATTNG(bf16_t, 128); else if (dh == 64) ATTNG(bf16_t, 64); else ATTNG(bf16_t, 32); }
+#undef ATTNG
     LAUNCH_CHECK();
   }
   if ((rc = gemm(c, w.o, c->xf_att, MT, &S))) return rc;
@@ -755,7 +760,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
       attr_done = true;                                                                                                 \
     }                                                                                                                   \
     k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
-        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP, atrace); \
+        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP, atrace, 1, 1); \
   } while (0)
     if (c->kv_f32) { if (dh == 128) ATTN2(float, 128); else if (dh == 64) ATTN2(float, 64); else ATTN2(float, 32); }
     else { if (dh == 128) ATTN2(bf16_t, 128); else if (dh == 64) ATTN2(bf16_t, 64); else ATTN2(bf16_t, 32); }
@@ -970,15 +975,6 @@ static int do_verify(eagle_ctx* c) {
     Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
     pass_ctx(c, pv);
     rc = target_forward2(c, pv, max_ctx(c), c->M, c->L, 0);
-  } else if (c->M <= 32) {
-    // Several sequences whose trees do not fit one 32-row pass together: one fast-path pass per sequence.  The
-    // weights are streamed once per sequence, which is still quicker than the 128-row general path on this machine
-    // (measured at the 7B shape, 4 x 26 rows: 20 ms against 33 ms).
-    for (int s = 0; s < c->n_active && !rc; ++s) {
-      Pass pv{PASS_VERIFY, c->M, 1, s, 0, 0, 0};
-      pass_ctx(c, pv);
-      rc = target_forward2(c, pv, c->h_ctx[s], c->M, c->L, 0);
-    }
   } else {
     Pass pv{PASS_VERIFY, c->M, c->n_active, 0, 0, 0, 0};
     pass_ctx(c, pv);

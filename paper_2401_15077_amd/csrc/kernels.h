@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
 }
 
 // ============================================================================ skinny weight-streaming GEMM
-// PT[s][n][m] = sum over the split's k range of W[n][k] * X[m][k];  W packed (NWP bf16 planes), X in XF layout
+// PT[s][m][n] = sum over the split's k range of W[n][k] * X[m][k];  W packed (NWP bf16 planes), X in XF layout
 // (NXP bf16 planes, MT 32-row tiles).  A block is 4 waves; wave w owns row-block blockIdx.x*4+w (32 rows of W)
 // and streams it once: every tile is one coalesced 1 KiB load that goes straight into the MFMA A operand.  The
 // block's X slice is staged in LDS (already in B-operand order).  Products kept: plane pairs (p, q) with
@@ -260,15 +260,17 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, siz
     }
   }
   if (rb < NRB) {
-    // accumulator register r of lane l holds W-row 8*(r/4) + 4*(l/32) + r%4, X-row l%32
-    float* out = PT + ((size_t)s * Npad + (size_t)rb * 32) * (MT * 32);
+    // accumulator register r of lane l holds W-row 8*(r/4) + 4*(l/32) + r%4, X-row l%32; partials are stored
+    // PT[s][m][n] (n fastest, which is how every epilogue kernel walks them): registers 4i..4i+3 are 16 contiguous bytes
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      float* out = PT + ((size_t)s * (MT * 32) + mt * 32 + (lane & 31)) * Npad + (size_t)rb * 32 + 4 * (lane >> 5);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int n = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        out[(size_t)n * (MT * 32) + mt * 32 + (lane & 31)] = acc[mt][r];
+      for (int i = 0; i < 4; ++i) {
+        f32x4 v; v.x = acc[mt][4 * i]; v.y = acc[mt][4 * i + 1]; v.z = acc[mt][4 * i + 2]; v.w = acc[mt][4 * i + 3];
+        *(f32x4*)(out + 8 * i) = v;
       }
+    }
   }
 }
 
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float*
       float v = h_in ? h_in[(size_t)r * d + k] : 0.f;
       if (PT) {
         float a = 0.f;
-        for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + k) * Mpad + r];
+        for (int s = 0; s < S; ++s) a += PT[((size_t)s * Mpad + r) * Npad + k];
         v += row_w ? row_w[r] * a : a;            // MoE: this expert's routing weight for the row (0 = not routed here)
       }
       if (bias) v += bias[k];
@@ -404,8 +406,8 @@ __global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev*
     int n2 = hd < H + KVH ? n1 + 1 : n1 + half;
     float a = 0.f, b = 0.f;
     for (int s = 0; s < S; ++s) {
-      a += PT[((size_t)s * Npad + n1) * Mpad + r];
-      b += PT[((size_t)s * Npad + n2) * Mpad + r];
+      a += PT[((size_t)s * Mpad + r) * Npad + n1];
+      b += PT[((size_t)s * Mpad + r) * Npad + n2];
     }
     if (hd < H + KVH) {   // q or k head: rotate
       float c = rope_cos[(size_t)ri.pos * half + i], sn = rope_sin[(size_t)ri.pos * half + i];
@@ -424,144 +426,7 @@ __global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev*
   }
 }
 
-// ============================================================================ tree-masked paged attention
-// One block = (kv split, query head, sequence x 32-row block).  Keys: cache slots [0, base) are visible to every
-// row; slot base+j is visible to a row iff bit j of its ancestor mask is set (tree passes) or j <= its own
-// relative index (causal passes).  Online softmax over 64-token tiles; partial (max, sum, acc) per split.
-template <typename CT, int DH>
-__global__ __launch_bounds__(256) void k_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
-                                              const float* __restrict__ Q, float* part_o, float* part_ml, int H,
-                                              int n_splits, int n_new /*slots past base that may be visible*/, float scale) {
-  constexpr int NRG = 256 / DH;            // row groups in the PV phase
-  constexpr int RPT = 32 / NRG;            // rows per thread in the PV phase
-  __shared__ float q_s[32][DH];
-  __shared__ float s_s[32][64];
-  __shared__ float alpha_s[32], m_s[32], l_s[32];
-  __shared__ int rel_s[32], causal_s[32];
-  __shared__ unsigned long long mask_s[32];
-  const int split = blockIdx.x, hd = blockIdx.y;
-  const int rblocks = (pass.rows_per_seq + 31) / 32;
-  const int seq_l = blockIdx.z / rblocks, rblk = blockIdx.z % rblocks;
-  const int r0 = seq_l * pass.rows_per_seq + rblk * 32;
-  const int R = min(32, pass.rows_per_seq - rblk * 32);
-  const int kvh = hd / (H / kv.n_kv_heads);
-  const int tid = threadIdx.x;
-  RowInfo r_first = row_info(pass, tree, st, r0);
-  const int seq = r_first.seq, base = r_first.base;
-  if (tid < 32) {
-    if (tid < R) {
-      RowInfo ri = row_info(pass, tree, st, r0 + tid);
-      rel_s[tid] = ri.rel; causal_s[tid] = ri.causal; mask_s[tid] = ri.mask;
-    }
-    m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f;
-  }
-  for (int i = tid; i < R * DH; i += 256) q_s[i / DH][i % DH] = Q[((size_t)(r0 + i / DH) * H + hd) * DH + i % DH];
-  const int T = base + n_new;
-  const int tps = ((T + n_splits - 1) / n_splits + 63) / 64 * 64;
-  const int t_begin = split * tps, t_end = min(T, t_begin + tps);
-  float acc[RPT];
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
-  const int d_own = tid % DH, rg = tid / DH;
-  __syncthreads();
-  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
-    // ---- scores: thread = (token tl, row quarter rq)
-    {
-      const int tl = tid & 63, rq = tid >> 6;
-      const int t = t0 + tl;
-      if (t < t_end) {
-        const CT* kp = (const CT*)kv.k + kv_offset(kv, seq, t, kvh);
-        float kr[DH];
-#pragma unroll
-        for (int d = 0; d < DH; ++d) kr[d] = cache_load(kp + d);
-        for (int r = rq; r < R; r += 4) {
-          float sdot = 0.f;
-#pragma unroll
-          for (int d = 0; d < DH; ++d) sdot += q_s[r][d] * kr[d];
-          bool vis = t < base;
-          if (!vis) {
-            int j = t - base;
-            vis = causal_s[r] ? (j <= rel_s[r]) : (j < 64 && ((mask_s[r] >> j) & 1ull));
-          }
-          s_s[r][tl] = vis ? sdot * scale : -INFINITY;
-        }
-      } else {
-        for (int r = rq; r < R; r += 4) s_s[r][tl] = -INFINITY;
-      }
-    }
-    __syncthreads();
-    // ---- running max / sum: wave w handles rows w, w+4, ...; lane = token
-    {
-      const int lane = tid & 63, w = tid >> 6;
-      for (int r = w; r < R; r += 4) {
-        float sv = s_s[r][lane];
-        float mx = wave_max(sv);
-        float m_old = m_s[r];
-        float m_new = fmaxf(m_old, mx);
-        float p = (m_new == -INFINITY) ? 0.f : __expf(sv - m_new);
-        float al = (m_new == -INFINITY || m_old == -INFINITY) ? (m_old == -INFINITY ? 0.f : 1.f) : __expf(m_old - m_new);
-        float ps = wave_sum(p);
-        s_s[r][lane] = p;
-        if (lane == 0) { m_s[r] = m_new; l_s[r] = l_s[r] * al + ps; alpha_s[r] = al; }
-      }
-    }
-    __syncthreads();
-    // ---- acc = acc*alpha + P.V : thread = (d_own, row group)
-    {
-      const int nt = min(64, t_end - t0);
-#pragma unroll
-      for (int i = 0; i < RPT; ++i) {
-        int r = rg + i * NRG;
-        if (r < R) acc[i] *= alpha_s[r];
-      }
-      for (int tl = 0; tl < nt; ++tl) {
-        const CT* vp = (const CT*)kv.v + kv_offset(kv, seq, t0 + tl, kvh);
-        float vv = cache_load(vp + d_own);
-#pragma unroll
-        for (int i = 0; i < RPT; ++i) {
-          int r = rg + i * NRG;
-          if (r < R) acc[i] += s_s[r][tl] * vv;
-        }
-      }
-    }
-    __syncthreads();
-  }
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    int r = rg + i * NRG;
-    if (r < R) part_o[(((size_t)(r0 + r) * H + hd) * n_splits + split) * DH + d_own] = acc[i];
-  }
-  if (tid < R) {
-    size_t o = (((size_t)(r0 + tid) * H + hd) * n_splits + split) * 2;
-    part_ml[o] = m_s[tid];
-    part_ml[o + 1] = l_s[tid];
-  }
-}
-
-// Merge the splits and write the attention output as the next GEMM's input (XF layout).  Block = one row.
-__global__ __launch_bounds__(256) void k_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                      int H, int DH, int n_splits, bf16_t* XF, int MT, int nplanes) {
-  int r = blockIdx.x;
-  const int K = H * DH, KS = K / 16;
-  for (int k8 = threadIdx.x * 8; k8 < K; k8 += blockDim.x * 8) {
-    int hd = k8 / DH, d0 = k8 % DH;
-    const float* ml = part_ml + ((size_t)r * H + hd) * n_splits * 2;
-    float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, ml[2 * s]);
-    float den = 0.f, x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int s = 0; s < n_splits; ++s) {
-      float ms = ml[2 * s];
-      if (ms == -INFINITY) continue;
-      float w = __expf(ms - m);
-      den += w * ml[2 * s + 1];
-      const float* o = part_o + (((size_t)r * H + hd) * n_splits + s) * DH + d0;
-      for (int t = 0; t < 8; ++t) x[t] += w * o[t];
-    }
-    float inv = den > 0.f ? 1.0f / den : 0.f;
-    for (int t = 0; t < 8; ++t) x[t] *= inv;
-    xf_store8(XF, r, k8, MT, KS, nplanes, x);
-  }
-}
+// (Tree-masked paged attention for both paths is k2_attn, in kernels2.h.)
 
 // ============================================================================ SwiGLU and logits epilogues
 // act[r][k] = silu(gate) * up with the fused matrix's row order (PACK_GATE / PACK_UP)   (F = d_ffn)
@@ -574,8 +439,8 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, in
   for (int t = 0; t < 8; ++t) {
     float g = 0.f, u = 0.f;
     for (int s = 0; s < S; ++s) {
-      g += PT[((size_t)s * Npad + pack_row_map(PACK_GATE, k8 + t, 0)) * Mpad + r];
-      u += PT[((size_t)s * Npad + pack_row_map(PACK_UP, k8 + t, 0)) * Mpad + r];
+      g += PT[((size_t)s * Mpad + r) * Npad + pack_row_map(PACK_GATE, k8 + t, 0)];
+      u += PT[((size_t)s * Mpad + r) * Npad + pack_row_map(PACK_UP, k8 + t, 0)];
     }
     x[t] = g / (1.0f + __expf(-g)) * u;
   }
@@ -600,7 +465,7 @@ __global__ __launch_bounds__(256) void k_logits(Pass pass, const TreeDev* tree, 
   int v = blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= V) return;
   float a = 0.f;
-  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Npad + v) * Mpad + r];
+  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Mpad + r) * Npad + v];
   out[dst + v] = a;
 }
 

@@ -700,19 +700,20 @@ template <typename CT, int DH>
 __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, SeqState st, KVCache kv,
                                                const float* __restrict__ Q, float* part_o, float* part_ml, int H,
                                                int n_splits, int n_new, float scale, int* counters, bf16_t* xf_out,
-                                               int nplanes, unsigned long long* trace) {
+                                               int nplanes, unsigned long long* trace, int MT, int rblocks) {
   constexpr int KSN = DH / 16;              // k-steps of the QK product
   constexpr int DB = DH / 32;               // 32-wide blocks of the head dimension
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_a[];
   float* o_s = (float*)smem_a;              // [4 waves][DH][32]
   float* ml_s = o_s + 4 * DH * 32;          // [4 waves][2][32]
   __shared__ int s_last;
-  const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z;
+  // blockIdx.z = (sequence of the pass, 32-row block of that sequence's rows); MT = 32-row tiles of the XF output
+  const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z / rblocks, rblk = blockIdx.z % rblocks;
   // optional time stamps: 0 entered, 1 keys/values consumed, 2 waves merged + partials written, 3 arrived, 4 splits merged
   unsigned long long* tr = (trace && threadIdx.x == 0 && seq_l == 0) ? trace + ((size_t)hd * gridDim.x + split) * 8 : nullptr;
   if (tr) tr[0] = wall_clock64();
-  const int r0 = seq_l * pass.rows_per_seq;
-  const int R = min(32, pass.rows_per_seq);
+  const int r0 = seq_l * pass.rows_per_seq + 32 * rblk;
+  const int R = min(32, pass.rows_per_seq - 32 * rblk);
   const int kvh = hd / (H / kv.n_kv_heads);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int q = lane & 31, hh = lane >> 5;
@@ -741,7 +742,8 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   }
   const int T = base + n_new;
   // the split boundaries depend on `base` only, so a row sees the same partition whatever else is in the pass
-  const int tps = ((base + 64 + n_splits - 1) / n_splits + 63) / 64 * 64;
+  const int span = base + max(64, (n_new + 63) / 64 * 64);   // passes with at most 64 new rows share one partition
+  const int tps = ((span + n_splits - 1) / n_splits + 63) / 64 * 64;
   const int t_begin = split * tps, t_end = min(T, t_begin + tps);
   float m_run = -INFINITY, l_run = 0.f;
   f32x16 oacc[DB];
@@ -860,7 +862,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     if (n_splits == 1) {
 #pragma unroll
       for (int t = 0; t < 8; ++t) o[t] *= inv;
-      xf_store8(xf_out, r0 + q2, hd * DH + 8 * c, 1, KSX, nplanes, o);
+      xf_store8(xf_out, r0 + q2, hd * DH + 8 * c, MT, KSX, nplanes, o);
     } else {
       const uint32_t po = (uint32_t)(((((size_t)(r0 + q2) * H + hd) * n_splits + split) * DH + 8 * c) * 4);
       f32x4 v0, v1;
@@ -879,7 +881,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
-    int* cnt = counters + seq_l * H + hd;
+    int* cnt = counters + blockIdx.z * H + hd;
     int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == n_splits - 1);
     if (s_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -914,7 +916,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
     for (int t = 0; t < CW; ++t) x[t] *= inv;
 #pragma unroll
-    for (int h8 = 0; h8 < CW / 8; ++h8) xf_store8(xf_out, r0 + r, hd * DH + d0 + 8 * h8, 1, KSX, nplanes, x + 8 * h8);
+    for (int h8 = 0; h8 < CW / 8; ++h8) xf_store8(xf_out, r0 + r, hd * DH + d0 + 8 * h8, MT, KSX, nplanes, x + 8 * h8);
   }
   if (tr) tr[4] = wall_clock64();
 }
