@@ -493,12 +493,12 @@ static int all_loaded(eagle_ctx* c) {
 template <int NWP, int NXP>
 static hipError_t launch_gemm_mt(const PackedW& w, const bf16_t* XF, float* PT, int MT, const GemmPlan& p, hipStream_t s) {
   dim3 grid((w.NRB + 3) / 4, p.S);
-  size_t lds = (size_t)NXP * MT * p.chunk * 1024;
+  size_t lds = (size_t)NXP * MT * GemmChunk<NXP>::CH * 1024;
   switch (MT) {
-    case 1: k_gemm<NWP, NXP, 1><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
-    case 2: k_gemm<NWP, NXP, 2><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
-    case 3: k_gemm<NWP, NXP, 3><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
-    default: k_gemm<NWP, NXP, 4><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, p.chunk, w.Npad); break;
+    case 1: k_gemm<NWP, NXP, 1><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
+    case 2: k_gemm<NWP, NXP, 2><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
+    case 3: k_gemm<NWP, NXP, 3><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
+    default: k_gemm<NWP, NXP, 4><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
   }
   return hipGetLastError();
 }

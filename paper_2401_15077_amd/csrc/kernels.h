@@ -200,16 +200,23 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
 // PT[s][m][n] = sum over the split's k range of W[n][k] * X[m][k];  W packed (NWP bf16 planes), X in XF layout
 // (NXP bf16 planes, MT 32-row tiles).  A block is 4 waves; wave w owns row-block blockIdx.x*4+w (32 rows of W)
 // and streams it once: every tile is one coalesced 1 KiB load that goes straight into the MFMA A operand.  The
-// block's X slice is staged in LDS (already in B-operand order).  Products kept: plane pairs (p, q) with
-// p + q < max(NWP, NXP); pieces beyond that are below fp32 resolution of the sum.
+// block's X slice passes through LDS (already in B-operand order) in chunks of CH k-steps.  While a chunk is being
+// multiplied, the next chunk's weight tiles AND activation tiles are already on their way into registers, so neither
+// HBM nor L2 latency is exposed between chunks.  Products kept: plane pairs (p, q) with p + q < max(NWP, NXP);
+// pieces beyond that are below fp32 resolution of the sum.
+template <int NXP> struct GemmChunk { static constexpr int CH = NXP == 2 ? 8 : 4; };   // k-steps per LDS stage
 template <int NWP, int NXP, int MT>
 __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, size_t w_plane_stride,
                                               const bf16_t* __restrict__ XF, float* __restrict__ PT, int NRB, int KS,
-                                              int ks_per_split, int chunk /*k-steps per LDS stage*/, int Npad) {
+                                              int ks_per_split, int Npad) {
+  constexpr int CH = GemmChunk<NXP>::CH;
+  constexpr int XT = NXP * MT * CH;                             // activation tiles (1 KiB each) per chunk
+  constexpr int XR = (XT * 64 + 255) / 256;                     // 16-byte pieces of them per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* xs = (u32x4*)smem;                                  // [NXP*MT][chunk][64] 16-byte lane chunks
+  u32x4* xs = (u32x4*)smem;                                     // [NXP*MT][CH][64] 16-byte lane chunks
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int rb = blockIdx.x * 4 + wave;
+  const int rb = min(blockIdx.x * 4 + wave, NRB - 1);           // waves past the end repeat the last block, store nothing
+  const bool live = blockIdx.x * 4 + wave < NRB;
   const int s = blockIdx.y;
   const int k_begin = s * ks_per_split;
   const int k_end = min(KS, k_begin + ks_per_split);
@@ -219,47 +226,67 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, siz
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  if (k_end <= k_begin) return;
+  const int klast = k_end - 1;
+  const u32x4* wbase = (const u32x4*)(Wp + (size_t)rb * KS * 512) + lane;
 
-  for (int c0 = k_begin; c0 < k_end; c0 += chunk) {
-    const int nk = min(chunk, k_end - c0);
-    __syncthreads();
-    // stage X: for every (plane, mt) a contiguous run of nk tiles
-    for (int pm = 0; pm < NXP * MT; ++pm) {
-      const u32x4* src = (const u32x4*)(XF + ((size_t)pm * KS + c0) * 512);
-      u32x4* dst = xs + (size_t)pm * chunk * 64;
-      for (int i = threadIdx.x; i < nk * 64; i += 256) dst[i] = src[i];
+  u32x4 xr[XR], ar[CH][NWP];
+  // piece i of a chunk: tile pm = i / (CH*64), k-step kk = (i / 64) % CH, lane-chunk i % 64 (the LDS order)
+  auto load_x = [&](int c0) {
+#pragma unroll
+    for (int u = 0; u < XR; ++u) {
+      const int i = min(u * 256 + (int)threadIdx.x, XT * 64 - 1);
+      const int pm = i / (CH * 64), kk = (i / 64) % CH, l = i & 63;
+      xr[u] = *((const u32x4*)(XF + ((size_t)pm * KS + min(c0 + kk, klast)) * 512) + l);
     }
-    __syncthreads();
-    if (rb < NRB) {
-      const u32x4* wsrc = (const u32x4*)(Wp + ((size_t)rb * KS + c0) * 512) + lane;
-      constexpr int U = (NWP == 1) ? 8 : 2;
-      for (int k0 = 0; k0 < nk; k0 += U) {
-        u32x4 a[U][NWP];
+  };
+  auto load_a = [&](int c0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+    for (int u = 0; u < CH; ++u)
 #pragma unroll
-          for (int p = 0; p < NWP; ++p)
-            if (k0 + u < nk) a[u][p] = *(const u32x4*)((const bf16_t*)(wsrc + (size_t)(k0 + u) * 64) + p * w_plane_stride);
+      for (int p = 0; p < NWP; ++p)
+        ar[u][p] = *(const u32x4*)((const bf16_t*)(wbase + (size_t)min(c0 + u, klast) * 64) + p * w_plane_stride);
+  };
+  auto store_x = [&]() {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (k0 + u < nk) {
+    for (int u = 0; u < XR; ++u) {
+      const int i = u * 256 + (int)threadIdx.x;
+      if (i < XT * 64) xs[i] = xr[u];
+    }
+  };
+  load_x(k_begin);
+  load_a(k_begin);
+  store_x();
+  __syncthreads();
+  for (int c0 = k_begin; c0 < k_end; c0 += CH) {
+    const int nk = min(CH, k_end - c0);
+    const bool more = c0 + CH < k_end;
+    u32x4 a[CH][NWP];
 #pragma unroll
-            for (int q = 0; q < NXP; ++q)
+    for (int u = 0; u < CH; ++u)
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt) {
-                u32x4 b = xs[((size_t)(q * MT + mt) * chunk + (k0 + u)) * 64 + lane];
+      for (int p = 0; p < NWP; ++p) a[u][p] = ar[u][p];
+    if (more) { load_x(c0 + CH); load_a(c0 + CH); }            // in flight while this chunk is multiplied
 #pragma unroll
-                for (int p = 0; p < NWP; ++p)
-                  if (p + q < PMAX)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][p]),
-                                                                      __builtin_bit_cast(bf16x8, b), acc[mt], 0, 0, 0);
-              }
+    for (int u = 0; u < CH; ++u) {
+      if (u < nk) {
+#pragma unroll
+        for (int q = 0; q < NXP; ++q)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 b = xs[((size_t)(q * MT + mt) * CH + u) * 64 + lane];
+#pragma unroll
+            for (int p = 0; p < NWP; ++p)
+              if (p + q < PMAX)
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][p]),
+                                                                  __builtin_bit_cast(bf16x8, b), acc[mt], 0, 0, 0);
           }
-        }
       }
     }
+    __syncthreads();                                            // every wave is done with this chunk's LDS
+    if (more) { store_x(); __syncthreads(); }
   }
-  if (rb < NRB) {
+  if (live) {
     // accumulator register r of lane l holds W-row 8*(r/4) + 4*(l/32) + r%4, X-row l%32; partials are stored
     // PT[s][m][n] (n fastest, which is how every epilogue kernel walks them): registers 4i..4i+3 are 16 contiguous bytes
 #pragma unroll
