@@ -389,15 +389,30 @@ __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float*
   int r = blockIdx.x;
   float ss = 0.f;
   // each thread owns chunks of 8 consecutive k
+  const float rw = row_w ? row_w[r] : 1.0f;    // MoE: this expert's routing weight for the row (0 = not routed here)
   for (int k8 = threadIdx.x * 8; k8 < d; k8 += blockDim.x * 8) {
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (PT) {
+      for (int s0 = 0; s0 < S; s0 += 8) {        // eight splits' worth of loads in flight, added in split order
+        f32x4 lo[8], hi[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float* src = PT + ((size_t)min(s0 + u, S - 1) * Mpad + r) * Npad + k8;
+          lo[u] = *(const f32x4*)src; hi[u] = *(const f32x4*)(src + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (s0 + u < S) {
+            a[0] += lo[u].x; a[1] += lo[u].y; a[2] += lo[u].z; a[3] += lo[u].w;
+            a[4] += hi[u].x; a[5] += hi[u].y; a[6] += hi[u].z; a[7] += hi[u].w;
+          }
+      }
+    }
+#pragma unroll
     for (int t = 0; t < 8; ++t) {
       int k = k8 + t;
       float v = h_in ? h_in[(size_t)r * d + k] : 0.f;
-      if (PT) {
-        float a = 0.f;
-        for (int s = 0; s < S; ++s) a += PT[((size_t)s * Mpad + r) * Npad + k];
-        v += row_w ? row_w[r] * a : a;            // MoE: this expert's routing weight for the row (0 = not routed here)
-      }
+      if (PT) v += row_w ? rw * a[t] : a[t];
       if (bias) v += bias[k];
       h_out[(size_t)r * d + k] = v;
       ss += v * v;
@@ -462,15 +477,29 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, in
   int r = blockIdx.y;
   int k8 = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
   if (k8 >= F) return;
-  float x[8];
-  for (int t = 0; t < 8; ++t) {
-    float g = 0.f, u = 0.f;
-    for (int s = 0; s < S; ++s) {
-      g += PT[((size_t)s * Mpad + r) * Npad + pack_row_map(PACK_GATE, k8 + t, 0)];
-      u += PT[((size_t)s * Mpad + r) * Npad + pack_row_map(PACK_UP, k8 + t, 0)];
+  // the 8 gate rows of this chunk are contiguous in the fused matrix (PACK_GATE), the 8 up rows sit 16 further
+  const int ng = pack_row_map(PACK_GATE, k8, 0);
+  float gs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, us[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < S; s0 += 4) {              // four splits' worth of loads in flight, added in split order
+    f32x4 g0[4], g1[4], u0[4], u1[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float* src = PT + ((size_t)min(s0 + q, S - 1) * Mpad + r) * Npad + ng;
+      g0[q] = *(const f32x4*)src; g1[q] = *(const f32x4*)(src + 4);
+      u0[q] = *(const f32x4*)(src + 16); u1[q] = *(const f32x4*)(src + 20);
     }
-    x[t] = g / (1.0f + __expf(-g)) * u;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (s0 + q < S) {
+        gs[0] += g0[q].x; gs[1] += g0[q].y; gs[2] += g0[q].z; gs[3] += g0[q].w;
+        gs[4] += g1[q].x; gs[5] += g1[q].y; gs[6] += g1[q].z; gs[7] += g1[q].w;
+        us[0] += u0[q].x; us[1] += u0[q].y; us[2] += u0[q].z; us[3] += u0[q].w;
+        us[4] += u1[q].x; us[5] += u1[q].y; us[6] += u1[q].z; us[7] += u1[q].w;
+      }
   }
+  float x[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) x[t] = gs[t] / (1.0f + __expf(-gs[t])) * us[t];
   xf_store8(XF, r, k8, MT, F / 16, nplanes, x);
 }
 
