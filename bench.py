@@ -74,7 +74,7 @@ def main() -> int:
         depth[v] = depth[int(par[v])] + 1
     D = max(depth)
     n_future = (K + W + 2) * (D + 1) + 8
-    max_seq = args.prompt + n_future + M + 16
+    max_seq = args.prompt + n_future + M + 16 + 64
     B = args.batch
     stochastic = args.temperature > 0.0
     t0 = time.time()
@@ -95,6 +95,18 @@ def main() -> int:
             futures[b].append(int(tk[b]))
     torch.cuda.synchronize()
     vanilla_tok_s = n_future * B / (time.time() - tv0)
+    if not stochastic and B > 1:
+        # With several sequences the verify rows take another kernel path than vanilla decoding, so the two can part
+        # at an arg-max near-tie.  The knob must hint at what THIS path will emit: an untimed speculative run without
+        # hints emits exactly that (the output of greedy speculation is decided by the verify logits alone).
+        eng.reset()
+        for b in range(B):
+            futures[b] = list(prompts[b]) + [eng.prefill(b, prompts[b])]
+        need = args.prompt + 1 + n_future
+        while min(len(f) for f in futures) < need and max(len(f) for f in futures) < need + 48:
+            toks, lens, _ = eng.step()
+            for b in range(B):
+                futures[b] += [int(t) for t in toks[b][:lens[b]]]
     future = futures[0]
     alpha = solve_alpha(args.tau, D)
     hint_seed = 20240126
