@@ -580,7 +580,11 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     float scale = 1.0f / std::sqrt((float)dh);
 #define ATTNG(CT, DH)                                                                                                   \
   do {                                                                                                                  \
-    HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   \
+    static bool attr_done = false;                                                                                      \
+    if (!attr_done) {                                                                                                   \
+      HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); \
+      attr_done = true;                                                                                                 \
+    }                                                                                                                   \
     k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
         pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf_att, c->NXP, nullptr, MT, rblocks); \
   } while (0)
