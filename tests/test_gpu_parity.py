@@ -198,6 +198,13 @@ def test_llama7b_full_depth_lockstep():
 
 
 
+def test_llama7b_twin_prompt512():
+    """The benchmark's context length (512-token prompt: 4 prefill chunks, 8 KV pages, 5 KV splits in attention) at
+    LLaMA2-7B widths with 2 target layers."""
+    st, toks, future = run_twin("llama2-7b", "T26", seed=7, n_layers=2, prompt_len=512, n_new=16, alpha=0.7773, max_seq=640)
+    assert toks[:512 + 16] == future[:512 + 16]
+
+
 def test_llama13b_twin_bf16_lockstep():
     """LLaMA2-13B widths (d 5120, 40 x 128 heads, FFN 13824): K slices that are not powers of two (5 and 14)."""
     st, toks, future = run_twin("llama2-13b", "T26", seed=3, n_layers=2, prompt_len=72, n_new=24, alpha=0.7773)
