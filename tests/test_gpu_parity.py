@@ -198,6 +198,22 @@ def test_llama7b_full_depth_lockstep():
 
 
 
+def test_tiny_bf16_kv_cache():
+    """The optional bf16 KV cache (keys and values rounded to nearest even when written) against the oracle's model
+    of it.  A cache entry whose fp32 value sits within rounding distance of a bf16 tie can round differently on the
+    two sides (one bf16 ulp = 0.4 % of that entry), hence the bf16 tolerance on an fp32 model."""
+    s, eng, orc = make_pair("tiny", "T15", seed=12, kv_dtype="bf16")
+    prompt = synth.prompt(12, 40, s.vocab)
+    check_prefill(eng, orc, prompt, TOL["bf16"])
+    st = Stats()
+    while len(orc.x) < len(prompt) + 40:
+        lockstep_step(eng, orc, st, TOL["bf16"])
+    assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x and st.excused_accepts <= 1
+    k, v = eng.get_kv_row(0, 1, 45)                     # stored values are bf16-representable
+    assert np.all((k.view(np.uint32) & 0xFFFF) == 0) and np.all((v.view(np.uint32) & 0xFFFF) == 0)
+    eng.close()
+
+
 def test_llama7b_twin_prompt512():
     """The benchmark's context length (512-token prompt: 4 prefill chunks, 8 KV pages, 5 KV splits in attention) at
     LLaMA2-7B widths with 2 target layers."""
