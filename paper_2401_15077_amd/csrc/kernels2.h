@@ -54,35 +54,9 @@ __device__ inline float row_rstd(const RowScale& rs, int m) {
   }
   return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
 }
-// Same value for all 32 rows at once, computed by a 512-thread block: thread (m, class c) loads its class's
-// groups (at most 16, all in flight), classes are combined through LDS.  out[32], tmp[16*32] in LDS.
-__device__ inline void block_rstd(const RowScale& rs, float* out, float* tmp) {
-  const int m = threadIdx.x & 31, c = threadIdx.x >> 5;
-  if (!rs.ssq) {
-    if (threadIdx.x < 32) out[threadIdx.x] = 1.0f;
-    __syncthreads();
-    return;
-  }
-  float v[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int g = c + 16 * i;
-    v[i] = g < rs.groups ? rs.ssq[g * 32 + m] : 0.f;
-  }
-  float a = 0.f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) a += v[i];
-  tmp[c * 32 + m] = a;
-  __syncthreads();
-  if (threadIdx.x < 32) {
-    float tot = 0.f;
-    for (int cc = 0; cc < 16; ++cc) tot += tmp[cc * 32 + threadIdx.x];
-    out[threadIdx.x] = 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
-  }
-  __syncthreads();
-}
-
-// the per-thread class partial of block_rstd, loaded early
+// The same value for all 32 rows at once, computed by a 512-thread block: thread (m, class c) loads its class's groups
+// (at most 16, all in flight) early in the kernel (rstd_class_partial); the classes are combined through LDS when the
+// epilogue needs the result (block_rstd_finish).
 __device__ inline float rstd_class_partial(const RowScale& rs) {
   if (!rs.ssq) return 0.f;
   const int m = threadIdx.x & 31, c = threadIdx.x >> 5;
