@@ -11,6 +11,8 @@ closed forms, brute force, exact enumeration, or an invariant the paper states.
 import itertools
 import math
 
+import os
+
 import numpy as np
 import pytest
 
@@ -118,11 +120,31 @@ def test_tree_rejects_bad_specs():
         Tree([-1, 2, 0], [0, 0, 0])
 
 
+def _golden(name):
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+
+
 def test_head_parameter_counts_match_the_paper():
-    # Sec. 4 "Training": 0.24 B, 0.37 B, 0.99 B trainable parameters for the 7B, 13B and 70B targets
-    assert round(synth.head_param_count(synth.SHAPES["llama2-7b"]) / 1e9, 2) == 0.24
-    assert round(synth.head_param_count(synth.SHAPES["llama2-13b"]) / 1e9, 2) == 0.37
-    assert round(synth.head_param_count(synth.SHAPES["llama2-70b"]) / 1e9, 2) == 0.99
+    # Sec. 4 "Training": trainable parameters of the head for the 7B, 13B and 70B targets (tests/golden)
+    rows = _golden("head_trainable_parameters.txt")
+    assert len(rows) == 3
+    for shape, printed in rows:
+        assert round(synth.head_param_count(synth.SHAPES[shape]) / 1e9, 2) == float(printed)
+
+
+def test_tree_facts_from_the_text():
+    # Sec. 3.1 / App. A.1: node counts, number of head passes and root branching stated in the text (tests/golden)
+    rows = _golden("draft_tree_facts.txt")
+    assert len(rows) == 3
+    for name, drafted, depth, root_k in rows:
+        t = Tree(*synth.TREES[name])
+        assert t.D == int(depth)
+        if drafted != "-":
+            assert t.M - 1 == int(drafted)
+        if root_k != "-":
+            assert len(t.children[0]) == int(root_k)
+        assert t.M - 1 >= t.D                      # m passes draft at least m tokens (more, unless a chain)
 
 
 # ----------------------------------------------------------------------------- whole greedy loop
