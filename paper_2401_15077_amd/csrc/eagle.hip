@@ -83,6 +83,7 @@ struct eagle_ctx {
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
   float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
+  bool fullk_on = true;                // wide GEMMs (QKV, gate/up, LM head) as whole-K work-groups without partials
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
   int n_cu = 256;
   // host mirror
@@ -395,6 +396,7 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
     if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "event creation failed"); }
   memset(&c->prof, 0, sizeof(c->prof));
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
+  if (const char* t = getenv("EAGLE_FULLK")) c->fullk_on = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   *out = c;
   return EAGLE_OK;
@@ -685,6 +687,19 @@ static hipError_t launch_k2(const Gemm2& g, size_t lds, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int NRMAX>
+static hipError_t launch_fk(const Gemm2& g, int grid, hipStream_t s) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)8 * NRMAX * 4096;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_fk<1, 2, NRMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  k2_gemm_fk<1, 2, NRMAX><<<grid, V2_THREADS, lds, s>>>(g);
+  return hipGetLastError();
+}
+
 // Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
 static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int* groups_out) {
   Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
@@ -706,7 +721,14 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
     HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used], c->stream));
   }
   hipError_t e;
-  if (c->f32) {
+  // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials)
+  const bool fullk = c->fullk_on && !c->f32 && !g.row_w && g.epi != EPI_RESID && w.NRB >= c->n_cu && g.dbg == 0;
+  if (fullk) {
+    const int grid = std::max(c->n_cu, (w.NRB + 3) / 4);
+    const int nrmax = (w.NRB + grid - 1) / grid;
+    g.trace = (g.trace && grid <= 1024) ? g.trace : nullptr;
+    e = nrmax <= 2 ? launch_fk<2>(g, grid, c->stream) : nrmax == 3 ? launch_fk<3>(g, grid, c->stream) : launch_fk<4>(g, grid, c->stream);
+  } else if (c->f32) {
     switch (p.RW) {
       case 1: e = launch_k2<3, 3, 1, 4>(g, p.lds, c->stream); break;
       case 2: e = launch_k2<3, 3, 2, 2>(g, p.lds, c->stream); break;

@@ -554,6 +554,203 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   if (tr) tr[4] = wall_clock64();
 }
 
+// ---- full-K variant for wide matrices (QKV, gate/up, LM head) ----------------------------------------------------------
+// A work-group owns up to 4 whole row blocks over ALL of K: no partial sums leave the chip, no arrival counter, no
+// last work-group.  The eight waves split K eight ways; a wave streams, per k-step, the weight tiles of the group's
+// row blocks from HBM AND the activation fragments of that k-step straight from L2 (every work-group reads the whole
+// X, 512 KB at d = 4096, which the 32 work-groups of an XCD share through its L2) -- no LDS staging, no barrier until
+// the end.  The waves' sums meet in LDS (k-part order) and the epilogue runs on them in place.  Costs more bytes per
+// CU than the split-K kernel and saves its publish / arrive / read-back round trips; pays off for matrices with at
+// least as many row blocks as there are CUs.
+// The activation fragments come through buffer loads: a lane whose row (lane % 32) is not a live row of the pass gets
+// an offset beyond the buffer, which the hardware answers with zeros WITHOUT touching memory -- a pass of M rows moves
+// M/32 of the fragment bytes (26/32 in a 26-node verify, 1/8 and less in the head's passes).
+template <int NWP, int NXP, int NR, int DEPTH>
+__device__ __forceinline__ void fk_stream(const bf16_t* __restrict__ XF, int KS, int M, int kb, int ke, const u32x4* const* wp,
+                                          size_t wps, f32x16* acc, int lane) {
+  constexpr int PMAX = NWP > NXP ? NWP : NXP;
+  if (ke <= kb) return;
+  const int klast = ke - 1;
+  u32x4 ta[DEPTH][NR][NWP], tb[DEPTH][NXP];
+  const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)XF, 0, NXP * KS * 1024, 0x00020000);
+  const uint32_t xlane = (lane & 31) < M ? (uint32_t)lane * 16u : 0x80000000u;   // dead rows: out of range
+#define FK_XLOAD(q, kk) __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, (uint32_t)(((q) * KS + (kk)) * 1024), 0))
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) {
+    const int kk = min(kb + dd, klast);
+#pragma unroll
+    for (int j = 0; j < NR; ++j)
+#pragma unroll
+      for (int p = 0; p < NWP; ++p) ta[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
+#pragma unroll
+    for (int q = 0; q < NXP; ++q) tb[dd][q] = FK_XLOAD(q, kk);
+  }
+  int k = kb;
+  for (; k + DEPTH < ke; k += DEPTH) {
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) {
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p)
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            if (p + q < PMAX)
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ta[dd][j][p]),
+                                                                __builtin_bit_cast(bf16x8, tb[dd][q]), acc[j], 0, 0, 0);
+      const int kn = min(k + dd + DEPTH, klast);
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p) ta[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kn * 64) + p * wps);
+#pragma unroll
+      for (int q = 0; q < NXP; ++q) tb[dd][q] = FK_XLOAD(q, kn);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) {
+    if (k + dd < ke) {
+#pragma unroll
+      for (int j = 0; j < NR; ++j)
+#pragma unroll
+        for (int p = 0; p < NWP; ++p)
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            if (p + q < PMAX)
+              acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ta[dd][j][p]),
+                                                                __builtin_bit_cast(bf16x8, tb[dd][q]), acc[j], 0, 0, 0);
+    }
+  }
+}
+#undef FK_XLOAD
+template <int NWP, int NXP, int NR>
+__device__ __forceinline__ void fk_stream_dispatch(int nr, const bf16_t* XF, int KS, int M, int kb, int ke, const u32x4* const* wp,
+                                                   size_t wps, f32x16* acc, int lane) {
+  constexpr int DEPTH = NWP == 1 ? (NR == 1 ? 8 : NR == 2 ? 6 : NR == 3 ? 5 : 4) : 2;   // ~24 KiB in flight per wave; deeper measured the same
+  if (nr == NR) fk_stream<NWP, NXP, NR, DEPTH>(XF, KS, M, kb, ke, wp, wps, acc, lane);
+  else if constexpr (NR > 1) fk_stream_dispatch<NWP, NXP, NR - 1>(nr, XF, KS, M, kb, ke, wp, wps, acc, lane);
+}
+
+// sum over the 8 waves of element (row n_local of row block j, token m) of the per-wave accumulators parked in LDS
+// as red[w][j][r][lane] (MFMA layout: r = 4*(n_local/8) + n_local%4, lane = m + 32*((n_local/4)%2)); k-part order
+__device__ inline float fk_sum(const float* red, int nrmax, int j, int n_local, int m) {
+  const int r = 4 * (n_local >> 3) + (n_local & 3), l = m + 32 * ((n_local >> 2) & 1);
+  float a = 0.f;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) a += red[(((size_t)w * nrmax + j) * 16 + r) * 64 + l];
+  return a;
+}
+
+template <int NWP, int NXP, int NRMAX>
+__global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float sh_small[16 * 33];
+  __shared__ float rstd_s[32];
+  float* red = (float*)smem;                                    // [8][NRMAX][16][64]
+  if (g.skip_flag && *g.skip_flag == 0) return;                 // MoE: no row selected this expert (uniform over the grid)
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
+  if (tr) tr[0] = wall_clock64();
+  const unsigned G = gridDim.x;
+  const int rb0 = (unsigned)blockIdx.x * (unsigned)g.NRB / G, rb1 = (unsigned)(blockIdx.x + 1) * (unsigned)g.NRB / G;
+  const int nr = rb1 - rb0;                                     // <= NRMAX (host)
+  const int kb = (unsigned)w * (unsigned)g.KS / 8u, ke = (unsigned)(w + 1) * (unsigned)g.KS / 8u;
+  const u32x4* wp[NRMAX];
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j) wp[j] = (const u32x4*)(g.W + (size_t)min(rb0 + j, g.NRB - 1) * g.KS * 512) + lane;
+  f32x16 acc[NRMAX];
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  // row facts and 1/rms inputs, requested before the stream
+  RowPre rp;
+  rp.valid = 0; rp.seq = 0; rp.pos = 0; rp.slot = 0; rp.dst = -1;
+  rp.ssq_part = rstd_class_partial(g.in_scale);
+  {
+    const int m = threadIdx.x & 31;
+    if (m < g.M) {
+      const RowInfo ri = row_info(g.pass, g.tree, g.st, m);
+      if (g.epi == EPI_QKV) { rp.valid = ri.valid; rp.seq = ri.seq; rp.pos = ri.pos; rp.slot = ri.slot; }
+      else if (g.epi == EPI_LOGITS && ri.valid) {
+        if (g.out_kind == 0) { if (ri.node >= 0) rp.dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
+        else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) rp.dst = (long)ri.seq * g.V;
+      }
+    }
+  }
+  fk_stream_dispatch<NWP, NXP, NRMAX>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane);
+  if (tr) tr[2] = wall_clock64() + (acc[0][0] == 123.456f ? 1 : 0);
+  // park every wave's sums in LDS
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j)
+    if (j < nr)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(((size_t)w * NRMAX + j) * 16 + r) * 64 + lane] = acc[j][r];
+  block_rstd_finish(g.in_scale, rp.ssq_part, rstd_s, sh_small);   // (contains the barriers that publish `red`)
+  __syncthreads();
+  const int m = threadIdx.x & 31, slot = threadIdx.x >> 5;     // 16 slots of 32 tokens
+  const bool live = m < g.M;
+  const float rs = live ? rstd_s[m] : 0.f;
+  if (g.epi == EPI_SWIGLU) {
+    // item = (row block j, half c2): 8 outputs f = rb*16 + 8*c2 .. +7 from gate rows 8*c2.. and up rows 16 + 8*c2..
+    for (int it = slot; it < nr * 2; it += 16) {
+      const int j = it >> 1, c2 = it & 1;
+      float x[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float gg = fk_sum(red, NRMAX, j, 8 * c2 + t, m) * rs, uu = fk_sum(red, NRMAX, j, 16 + 8 * c2 + t, m) * rs;
+        x[t] = gg / (1.0f + __expf(-gg)) * uu;
+      }
+      if (live) xf_store8(g.xf_out, m, (rb0 + j) * 16 + 8 * c2, 1, g.xf_KS, NXP, x);
+    }
+  } else if (g.epi == EPI_QKV) {
+    const int dh = g.kv.head_dim, half = dh >> 1, KVH = g.kv.n_kv_heads, H = g.H;
+    // item = (row block j, rotate-half pair pp of 16): rows 2pp, 2pp + 1 of the block
+    for (int it = slot; it < nr * 16; it += 16) {
+      const int j = it >> 4, pp = it & 15;
+      const int n = (rb0 + j) * 32 + 2 * pp;
+      if (n >= g.N || !live) continue;
+      float a = fk_sum(red, NRMAX, j, 2 * pp, m) * rs, b = fk_sum(red, NRMAX, j, 2 * pp + 1, m) * rs;
+      const int hd = n / dh, pr = n % dh;
+      int d1, d2;
+      if (hd < H + KVH) {        // q or k head: the two rows are a rotate-half pair
+        const int i = pr >> 1;
+        const float cs = g.rope_cos[(size_t)rp.pos * half + i], sn = g.rope_sin[(size_t)rp.pos * half + i];
+        const float a2 = a * cs - b * sn, b2 = b * cs + a * sn;
+        a = a2; b = b2; d1 = i; d2 = i + half;
+      } else { d1 = pr; d2 = pr + 1; }
+      if (hd < H) {
+        float* q = g.Q + ((size_t)m * H + hd) * dh;
+        q[d1] = a; q[d2] = b;
+      } else if (rp.valid) {
+        const int kvh = (hd - H) % KVH;
+        const size_t off = kv_offset(g.kv, rp.seq, rp.slot, kvh);
+        void* base = hd < H + KVH ? g.kv.k : g.kv.v;
+        if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
+        else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
+      }
+    }
+  } else {                                                      // EPI_LOGITS
+    const int nend = min(g.N, g.V);
+    const bool vec = (g.V & 3) == 0;
+    for (int it = slot; it < nr * 8; it += 16) {                // item = (row block j, quad of 4 rows)
+      const int j = it >> 3, qd = it & 7;
+      const int n = (rb0 + j) * 32 + 4 * qd;
+      if (rp.dst < 0 || n >= nend) continue;
+      float v[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] = fk_sum(red, NRMAX, j, 4 * qd + t, m) * rs;
+      if (vec && n + 4 <= nend) { f32x4 o; o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3]; *(f32x4*)(g.logits + rp.dst + n) = o; }
+      else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) if (n + t < nend) g.logits[rp.dst + n + t] = v[t];
+      }
+    }
+  }
+  if (tr) tr[4] = wall_clock64();
+}
+
 // Rows of a pass that need no GEMM in front: h = embedding of the row's token.  Writes h, XF(h * gain) and the
 // partial sums of squares, one column slab per block (the same outputs a residual epilogue produces).
 template <typename EmbT, int NXP>
