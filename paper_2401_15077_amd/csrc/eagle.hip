@@ -83,6 +83,7 @@ struct eagle_ctx {
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
   float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
+  bool xk_on = true;                   // other bf16 GEMMs: streamed-activation split-K where the fetch model prefers it
   bool fullk_on = true;                // wide GEMMs (QKV, gate/up, LM head) as whole-K work-groups without partials
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
   int n_cu = 256;
@@ -111,6 +112,23 @@ static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
 
 // Work split of the fast-path GEMM: S K-slices x `groups` row groups = one work-group each; inside a work-group
 // `lanes` x `kparts` waves (product 8): a wave owns every lanes-th row block of the group over one k-part.
+// Work split of the split-K kernel with streamed activations: S slices x groups of at most 4 row blocks, chosen by a
+// fetch model in KiB per work-group (weights + the live part of the X slice + twice the partials the last work-group
+// of a row group reads back, which sit on the critical path of one CU).  Depends on the matrix shape only.
+struct PlanXK { int S, groups, nrmax; long cost; };
+static PlanXK plan_xk(int NRB, int KS, int NXP, int n_cu, size_t pt_floats_per_slice, size_t pt_floats) {
+  PlanXK best; best.S = 0; best.groups = 0; best.nrmax = 0; best.cost = -1;
+  for (int S = 1; S <= 16; ++S) {
+    const int groups = std::min(NRB, n_cu / S);
+    if (groups < 1) break;
+    const int nrm = (NRB + groups - 1) / groups, kt = (KS + S - 1) / S;
+    if (nrm > 4 || kt < 16 || (size_t)S * pt_floats_per_slice > pt_floats) continue;
+    const long cost = (long)nrm * kt + (long)NXP * kt * 4 / 5 + 2L * S * nrm * 4;
+    if (best.cost < 0 || cost < best.cost) { best.S = S; best.groups = groups; best.nrmax = nrm; best.cost = cost; }
+  }
+  return best;
+}
+
 struct Plan2 { int S, groups, lanes, kparts, RW, kt_max; size_t lds; };
 static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
   Plan2 p;
@@ -397,6 +415,7 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   memset(&c->prof, 0, sizeof(c->prof));
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
   if (const char* t = getenv("EAGLE_FULLK")) c->fullk_on = atoi(t) != 0;
+  if (const char* t = getenv("EAGLE_XK")) c->xk_on = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   *out = c;
   return EAGLE_OK;
@@ -700,6 +719,19 @@ static hipError_t launch_fk(const Gemm2& g, int grid, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int NRMAX>
+static hipError_t launch_xk(const Gemm2& g, hipStream_t s) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)8 * NRMAX * 4096;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_xk<1, 2, NRMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  k2_gemm_xk<1, 2, NRMAX><<<g.groups * g.S, V2_THREADS, lds, s>>>(g);
+  return hipGetLastError();
+}
+
 // Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
 static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int* groups_out) {
   Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
@@ -723,7 +755,21 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   hipError_t e;
   // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials)
   const bool fullk = c->fullk_on && !c->f32 && !g.row_w && g.epi != EPI_RESID && w.NRB >= c->n_cu && g.dbg == 0;
-  if (fullk) {
+  // other matrices of the bf16 configuration: split-K, with the activations either staged in LDS (plan2) or streamed
+  // (plan_xk), whichever the fetch model prices lower
+  PlanXK px; px.S = 0;
+  if (!fullk && c->xk_on && !c->f32 && g.dbg == 0) {
+    px = plan_xk(w.NRB, w.KS, c->NXP, c->n_cu, (size_t)w.Npad * 32, c->pt2_floats);
+    const int kt_s = (w.KS + p.S - 1) / p.S;
+    const long staged = (long)R * kt_s + (long)c->NXP * kt_s + 2L * p.S * R * 4 + 40;
+    if (px.S > 0 && px.cost >= staged) px.S = 0;
+  }
+  if (px.S > 0) {
+    g.S = px.S; g.groups = px.groups;
+    if (groups_out) *groups_out = px.groups;
+    g.trace = (g.trace && px.groups * px.S <= 1024) ? g.trace : nullptr;
+    e = px.nrmax <= 2 ? launch_xk<2>(g, c->stream) : px.nrmax == 3 ? launch_xk<3>(g, c->stream) : launch_xk<4>(g, c->stream);
+  } else if (fullk) {
     const int grid = std::max(c->n_cu, (w.NRB + 3) / 4);
     const int nrmax = (w.NRB + grid - 1) / grid;
     g.trace = (g.trace && grid <= 1024) ? g.trace : nullptr;

@@ -751,6 +751,97 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
   if (tr) tr[4] = wall_clock64();
 }
 
+// ---- split-K with streamed activations (narrow matrices with a long K: O, down) ------------------------------------------
+// The split-K kernel above keeps its X slice in LDS, so a long K forces many slices (11 at K = 11008) and the last
+// work-group of a row group reads that many partials on one CU.  Here the slice is streamed from L2 like in the
+// whole-K kernel (8 waves split the slice's k-steps, sums meet in LDS), so S is free: a few slices of a few row
+// blocks each.  The work-group then costs its weights plus M/32 of its X slice in fetches, but exchanges only
+// S x (row blocks) x 4 KiB per row group, and nothing waits for an LDS fill before the weight stream starts.
+// Partials, arrival counter and epilogues are those of k2_gemm.
+template <int NWP, int NXP, int NRMAX>
+__global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float sh_small[16 * 33];
+  __shared__ float rstd_s[32];
+  __shared__ int s_last;
+  float* red = (float*)smem;                                    // [8][NRMAX][16][64]
+  if (g.skip_flag && *g.skip_flag == 0) return;                 // uniform over the whole grid
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
+  if (tr) tr[0] = wall_clock64();
+  const unsigned uS = g.S, ugroups = g.groups, uNRB = g.NRB, uKS = g.KS;
+  const int s = blockIdx.x % uS, grp = blockIdx.x / uS;
+  const int rb0 = (unsigned)grp * uNRB / ugroups, rb1 = (unsigned)(grp + 1) * uNRB / ugroups;
+  const int nr = rb1 - rb0;                                     // <= NRMAX (host)
+  const int ks0 = (unsigned)s * uKS / uS, ks1 = (unsigned)(s + 1) * uKS / uS, kt = ks1 - ks0;
+  const int kb = ks0 + (unsigned)w * (unsigned)kt / 8u, ke = ks0 + (unsigned)(w + 1) * (unsigned)kt / 8u;
+  const u32x4* wp[NRMAX];
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j) wp[j] = (const u32x4*)(g.W + (size_t)min(rb0 + j, g.NRB - 1) * g.KS * 512) + lane;
+  f32x16 acc[NRMAX];
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  RowPre rp;
+  rp.valid = 0; rp.seq = 0; rp.pos = 0; rp.slot = 0; rp.dst = -1;
+  rp.ssq_part = rstd_class_partial(g.in_scale);
+  {
+    const int m = threadIdx.x & 31;
+    if (m < g.M && (g.epi == EPI_QKV || g.epi == EPI_LOGITS)) {
+      const RowInfo ri = row_info(g.pass, g.tree, g.st, m);
+      if (g.epi == EPI_QKV) { rp.valid = ri.valid; rp.seq = ri.seq; rp.pos = ri.pos; rp.slot = ri.slot; }
+      else if (ri.valid) {
+        if (g.out_kind == 0) { if (ri.node >= 0) rp.dst = ((long)ri.seq * g.tree->M + ri.node) * g.V; }
+        else if (!(g.only_last_row && ri.rel != g.pass.chunk_n - 1 && g.pass.kind != PASS_VANILLA)) rp.dst = (long)ri.seq * g.V;
+      }
+    }
+  }
+  fk_stream_dispatch<NWP, NXP, NRMAX>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane);
+  if (tr) tr[2] = wall_clock64() + (acc[0][0] == 123.456f ? 1 : 0);
+#pragma unroll
+  for (int j = 0; j < NRMAX; ++j)
+    if (j < nr)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(((size_t)w * NRMAX + j) * 16 + r) * 64 + lane] = acc[j][r];
+  __syncthreads();
+  // the waves share the sum and the publication: item = (row block j, register quad i) -> rows 8i + 4(lane/32) + 0..3
+  for (int it = w; it < nr * 4; it += 8) {
+    const int j = it >> 2, i = it & 3;
+    float v[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      float a = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) a += red[(((size_t)ww * NRMAX + j) * 16 + 4 * i + t) * 64 + lane];
+      v[t] = a;
+    }
+    f32x4 o; o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3];
+    coh_store16(g.PT, pt_quad_bytes(s, g.Npad, (rb0 + j) * 32 + 8 * i + 4 * (lane >> 5), lane & 31), o);
+  }
+  if (tr) tr[3] = wall_clock64();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == g.S - 1);
+    if (s_last) __hip_atomic_store(g.counters + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
+  if (n1 <= n0) return;
+  if (g.epi != EPI_RESID) block_rstd_finish(g.in_scale, rp.ssq_part, rstd_s, sh_small);
+  switch (g.epi) {
+    case EPI_QKV: epilogue_qkv<NXP>(g, n0, n1, rstd_s, rp); break;
+    case EPI_RESID: epilogue_resid<NXP>(g, grp, n0, n1, sh_small); break;
+    case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
+    default: epilogue_logits(g, n0, n1, rstd_s, rp); break;
+  }
+  if (tr) tr[4] = wall_clock64();
+}
+
 // Rows of a pass that need no GEMM in front: h = embedding of the row's token.  Writes h, XF(h * gain) and the
 // partial sums of squares, one column slab per block (the same outputs a residual epilogue produces).
 template <typename EmbT, int NXP>
