@@ -89,6 +89,16 @@ __device__ inline void block_rstd_finish(const RowScale& rs, float part, float* 
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
+// Before a work-group announces its coherent stores through an arrival counter, every wave waits until its own
+// vector-memory stores have been acknowledged.  A work-group-scope release fence alone does not do that on this
+// target (waves of one work-group share a CU, so the compiler emits no vector-memory wait for it), and the stores
+// go to other L2 channels than the counter: without the wait the counter can be seen before the data.
+// s_waitcnt 0x0F70 = vmcnt(0), expcnt and lgkmcnt left alone.
+__device__ __forceinline__ void publish_wait() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 struct Gemm2 {
   const bf16_t* W; size_t wps; int NRB, KS, Npad, N;
   const bf16_t* XF;                       // NXP planes of KS tiles (one 32-row tile per k-step)
@@ -530,7 +540,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
       }
   }
   // publish the partials; the last work-group of this row group to arrive finishes the job
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // every coherent store above has been acknowledged
+  publish_wait();                                               // every coherent store above has been acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
     int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -820,7 +830,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
     coh_store16(g.PT, pt_quad_bytes(s, g.Npad, (rb0 + j) * 32 + 8 * i + 4 * (lane >> 5), lane & 31), o);
   }
   if (tr) tr[3] = wall_clock64();
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  publish_wait();
   __syncthreads();
   if (threadIdx.x == 0) {
     int old = __hip_atomic_fetch_add(g.counters + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1140,7 +1150,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     coh_store(part_ml + ofs, mm);
     coh_store(part_ml + ofs + 1, L);
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  publish_wait();
   __syncthreads();
   if (tid == 0) {
     int* cnt = counters + blockIdx.z * H + hd;
