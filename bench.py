@@ -111,10 +111,18 @@ def main() -> int:
     alpha = solve_alpha(args.tau, D)
     hint_seed = 20240126
 
+    hist = np.zeros(D + 2, np.int64)                  # accepted draft tokens per sequence and step (timed run)
+    prefill_ms = [0.0]
+
     def run(mode: int, steps: int):
         eng.reset()
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
         for b in range(B):
             eng.prefill(b, prompts[b])
+        torch.cuda.synchronize()
+        prefill_ms[0] = (time.perf_counter() - tp) * 1e3
+        for b in range(B):
             if not stochastic:
                 eng.set_hint(b, futures[b], alpha, HINT_BIAS, hint_seed + b)
         eng.set_profiling(0)
@@ -128,6 +136,9 @@ def main() -> int:
         for _ in range(steps):
             _, lens, _ = eng.step()
             emitted += int(lens.sum())
+            if mode == 0:
+                for b in range(B):
+                    hist[int(lens[b]) - 1] += 1
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
         prof = eng.get_profile(reset=True)
@@ -135,6 +146,13 @@ def main() -> int:
         return dt, emitted, prof
 
     dt, emitted, _ = run(0, K)                       # the timed region: exactly K steps
+    prefill_ms_timed = prefill_ms[0]
+    # acceptance rate by depth: of the steps whose accepted path reached depth n, the share that also accepted a token
+    # at depth n + 1 -- a token drafted from an input holding n predicted features.  With `--tree chain5` this is the
+    # paper's n-alpha (Metrics paragraph of the experiments section, defined on chain drafts); on tree drafts it is the
+    # per-depth acceptance of the best of the node's children.
+    reached = np.cumsum(hist[::-1])[::-1]             # reached[n] = steps with at least n accepted draft tokens
+    accept_by_depth = [float(reached[n + 1] / reached[n]) if reached[n] > 0 else None for n in range(D)]
     stale = False
     if not stochastic:
         for b in range(B):
@@ -169,8 +187,9 @@ def main() -> int:
         "tau": emitted / K / B, "verify_ms": verify_ms, "draft_ms": draft_ms, "accept_ms": accept_ms,
         "verify_hbm_frac": verify_bytes / (verify_ms * 1e-3) / 8e12 if verify_ms > 0 else None,
         "verify_bytes": verify_bytes, "vanilla_tokens_per_s": vanilla_tok_s, "hint_stale": bool(stale),
-        "load_s": t_load,
-        "roofline": {"bound": "hbm", "kernel": "k2_gemm + k2_gemm_fk (fused weight-streaming GEMMs, all launches of the timed steps)",
+        "load_s": t_load, "prefill_ms": prefill_ms_timed, "prefill_tokens_per_s": B * args.prompt / (prefill_ms_timed * 1e-3),
+        "accept_rate_by_depth": accept_by_depth,
+        "roofline": {"bound": "hbm", "kernel": "k2_gemm_fk + k2_gemm_xk (fused weight-streaming GEMMs: whole-K and streamed split-K; all launches of the timed steps)",
                      "achieved": gemm_gbs, "peak": 8000.0, "unit": "GB/s", "frac": gemm_gbs / 8000.0, "traffic": traffic,
                      "launches": int(prof2["gemm_launches"]),
                      "avg_launch_us": gemm_ms * 1e3 / n_launch,
