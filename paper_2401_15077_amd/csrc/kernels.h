@@ -920,14 +920,24 @@ __global__ __launch_bounds__(256) void k_router(const float* xnorm, const float*
   __shared__ float lg[64];
   const int r = blockIdx.x;
   float rstd = 1.f;
-  if (!xnorm) {
-    float tot = 0.f;
-    for (int c = 0; c < 16; ++c) {
+  if (!xnorm) {                                  // same class order as every other consumer of these partial sums
+    if (threadIdx.x < 16) {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int g = (int)threadIdx.x + 16 * i;
+        v[i] = g < ssq_groups ? ssq[g * 32 + r] : 0.f;
+      }
       float a = 0.f;
-      for (int g = c; g < ssq_groups; g += 16) a += ssq[g * 32 + r];
-      tot += a;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) a += v[i];
+      sh[threadIdx.x] = a;
     }
+    __syncthreads();
+    float tot = 0.f;
+    for (int c = 0; c < 16; ++c) tot += sh[c];
     rstd = 1.0f / sqrtf(tot * inv_d + eps);
+    __syncthreads();                             // sh is reused by block_sum below
   }
   for (int e = 0; e < E; ++e) {
     float a = 0.f;

@@ -42,17 +42,31 @@ struct RowScale {            // 1/rms of the rows that produced the GEMM input; 
   int groups;
   float inv_d, eps;
 };
-// Sum of squares of row m = sum over 16 strided classes of groups, classes added in order (one fixed order for
-// every caller, whether one thread walks it or a block shares the loads).
-__device__ inline float row_rstd(const RowScale& rs, int m) {
-  if (!rs.ssq) return 1.0f;
-  float tot = 0.f;
-  for (int c = 0; c < 16; ++c) {
+// 1/rms of row m from the per-group partial sums of squares: 16 strided classes of groups, classes added in order
+// (one fixed order for every caller).  The block shares the loads: threads 0..15 each own a class (at most 16 groups,
+// all loads in flight), thread 0 adds the classes.  tmp: 17 floats of LDS.  Every thread of the block must call it.
+__device__ inline float block_row_rstd(const float* ssq, int groups, float inv_d, float eps, int m, float* tmp) {
+  if (!ssq) return 1.0f;
+  if (threadIdx.x < 16) {
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int g = (int)threadIdx.x + 16 * i;
+      v[i] = g < groups ? ssq[g * 32 + m] : 0.f;
+    }
     float a = 0.f;
-    for (int g = c; g < rs.groups; g += 16) a += rs.ssq[g * 32 + m];
-    tot += a;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a += v[i];
+    tmp[threadIdx.x] = a;
   }
-  return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+    for (int c = 0; c < 16; ++c) tot += tmp[c];
+    tmp[16] = 1.0f / sqrtf(tot * inv_d + eps);
+  }
+  __syncthreads();
+  return tmp[16];
 }
 // The same value for all 32 rows at once, computed by a 512-thread block: thread (m, class c) loads its class's groups
 // (at most 16, all in flight) early in the kernel (rstd_class_partial); the classes are combined through LDS when the
@@ -896,9 +910,10 @@ __global__ __launch_bounds__(256) void k2_embed(Pass pass, const TreeDev* tree, 
 
 // features[m][k] = h[m][k] * rstd[m] * gain[k]   (the target's final RMSNorm, Sec. 2: f is what the LM head reads)
 __global__ __launch_bounds__(256) void k2_features(const float* h, RowScale rs, const float* gain, int M, int d, float* out) {
+  __shared__ float tmp[17];
   const int m = blockIdx.x;
   if (m >= M) return;
-  const float r = row_rstd(rs, m);
+  const float r = block_row_rstd(rs.ssq, rs.groups, rs.inv_d, rs.eps, m, tmp);
   for (int k = threadIdx.x; k < d; k += blockDim.x) out[(size_t)m * d + k] = h[(size_t)m * d + k] * r * gain[k];
 }
 
