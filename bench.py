@@ -48,6 +48,7 @@ def main() -> int:
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--tau", type=float, default=3.5)
     ap.add_argument("--tree", default="T26")
+    ap.add_argument("--alpha", type=float, default=None, help="per-position hit probability of the knob (default: solved from --tau for this tree depth)")
     ap.add_argument("--seed", type=int, default=2)
     ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (each with its own prompt and knob)")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic tree acceptance, no knob (natural acceptance)")
@@ -108,7 +109,7 @@ def main() -> int:
             for b in range(B):
                 futures[b] += [int(t) for t in toks[b][:lens[b]]]
     future = futures[0]
-    alpha = solve_alpha(args.tau, D)
+    alpha = args.alpha if args.alpha is not None else solve_alpha(args.tau, D)
     hint_seed = 20240126
 
     hist = np.zeros(D + 2, np.int64)                  # accepted draft tokens per sequence and step (timed run)

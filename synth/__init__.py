@@ -172,6 +172,7 @@ _T15 = ["0", "1",
         "0000", "0001", "0010", "0100"]
 _T10 = ["0", "1", "00", "01", "10", "11", "000", "001", "010", "100"]   # 10 drafted tokens in 3 draft passes
 _CHAIN5 = ["0", "00", "000", "0000", "00000"]
+_T8 = ["0", "1", "00", "01", "10", "000", "0000"]   # 8 nodes with the root, depth 4: four sequences fill one 32-row verify pass
 
 
 def tree_from_paths(paths: List[str]) -> Tuple[np.ndarray, np.ndarray]:
@@ -200,6 +201,7 @@ TREES: Dict[str, Tuple[np.ndarray, np.ndarray]] = {
     "T15": tree_from_paths(_T15),
     "T10": tree_from_paths(_T10),
     "chain5": tree_from_paths(_CHAIN5),
+    "T8": tree_from_paths(_T8),
     "root": tree_from_paths([]),             # degenerate: no drafts at all, a step is one vanilla step
     "B63": tree_from_paths(_full_binary(5)),  # full binary tree of depth 5: 63 nodes (more rows than one 32-row pass)
 }

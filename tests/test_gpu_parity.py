@@ -176,6 +176,33 @@ def test_batch4_lockstep():
     eng.close()
 
 
+@pytest.mark.parametrize("shape_name,n_layers,tol_key,steps", [("tiny", None, "fp32", 12), ("llama2-7b", 2, "bf16", 6)])
+def test_batch4_small_tree_one_verify_pass(shape_name, n_layers, tol_key, steps):
+    """Four sequences with an 8-node tree (the smaller tree for larger batches): the 4 x 8 verify rows fill exactly one
+    32-row pass, so verify runs through the fused fast-path kernels with four sequences' rows side by side."""
+    s = synth.SHAPES[shape_name]
+    if n_layers is not None:
+        s = s.twin(n_layers)
+    par, rk = synth.TREES["T8"]
+    eng = pkg.Eagle(s, par, rk, max_batch=4, max_seq=160)
+    eng.load_weights(synth.iter_weights(s, 5, synth.device_fmt(s)))
+    W = synth.make_weights(s, 5, synth.oracle_fmt(s))
+    orcs, sts = [], []
+    for b in range(4):
+        orc = Oracle(s, W, par, rk, max_seq=160, seq_id=b)
+        prompt = synth.prompt(5, 12 + 7 * b, s.vocab, stream=b)
+        check_prefill(eng, orc, prompt, TOL[tol_key], seq=b)
+        orcs.append(orc); sts.append(Stats())
+    for _ in range(steps):
+        lockstep_step_batch(eng, orcs, sts, TOL[tol_key])
+    for b in range(4):
+        assert list(eng.get_buffer(pkg.BUF_TOKENS, b)) == orcs[b].x
+        assert sts[b].max_logit_err <= TOL[tol_key]
+        if tol_key == "fp32":
+            assert sts[b].excused_accepts == 0
+    eng.close()
+
+
 def test_moe_stochastic_lockstep():
     """The Mixtral-shaped configuration's mode in small: MoE target and head, temperature 1, seeded draws."""
     s, eng, orc = make_pair("mini-moe", "T15", seed=8, temperature=1.0, rng_seed=77, n_layers=2, dtype=np.float64)
