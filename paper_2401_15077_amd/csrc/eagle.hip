@@ -84,6 +84,7 @@ struct eagle_ctx {
   float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
   bool xk_on = true;                   // other bf16 GEMMs: streamed-activation split-K where the fetch model prefers it
+  bool half_on = true;                 // whole-K QKV: half-row-block work split where it balances better
   bool fullk_on = true;                // wide GEMMs (QKV, gate/up, LM head) as whole-K work-groups without partials
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
   int n_cu = 256;
@@ -416,6 +417,7 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
   if (const char* t = getenv("EAGLE_FULLK")) c->fullk_on = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_XK")) c->xk_on = atoi(t) != 0;
+  if (const char* t = getenv("EAGLE_HALF")) c->half_on = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   *out = c;
   return EAGLE_OK;
@@ -706,16 +708,16 @@ static hipError_t launch_k2(const Gemm2& g, size_t lds, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int NRMAX>
+template <int NRMAX, bool HALF = false>
 static hipError_t launch_fk(const Gemm2& g, int grid, hipStream_t s) {
   static bool attr_set = false;
   const size_t lds = (size_t)8 * NRMAX * 4096;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_fk<1, 2, NRMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_fk<1, 2, NRMAX, HALF>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  k2_gemm_fk<1, 2, NRMAX><<<grid, V2_THREADS, lds, s>>>(g);
+  k2_gemm_fk<1, 2, NRMAX, HALF><<<grid, V2_THREADS, lds, s>>>(g);
   return hipGetLastError();
 }
 
@@ -773,7 +775,13 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
     const int grid = std::max(c->n_cu, (w.NRB + 3) / 4);
     const int nrmax = (w.NRB + grid - 1) / grid;
     g.trace = (g.trace && grid <= 1024) ? g.trace : nullptr;
-    e = nrmax <= 2 ? launch_fk<2>(g, grid, c->stream) : nrmax == 3 ? launch_fk<3>(g, grid, c->stream) : launch_fk<4>(g, grid, c->stream);
+    // QKV: split by half row blocks where that lowers the largest share (3 halves instead of 2 blocks at d = 4096);
+    // a run of u halves touches at most u/2 + 1 blocks
+    const int umax = (2 * w.NRB + grid - 1) / grid;
+    const bool half = c->half_on && g.epi == EPI_QKV && umax < 2 * nrmax && umax / 2 + 1 <= 2 &&
+                      (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
+    if (half) e = launch_fk<2, true>(g, grid, c->stream);
+    else e = nrmax <= 2 ? launch_fk<2>(g, grid, c->stream) : nrmax == 3 ? launch_fk<3>(g, grid, c->stream) : launch_fk<4>(g, grid, c->stream);
   } else if (c->f32) {
     switch (p.RW) {
       case 1: e = launch_k2<3, 3, 1, 4>(g, p.lds, c->stream); break;

@@ -589,9 +589,15 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
 // The activation fragments come through buffer loads: a lane whose row (lane % 32) is not a live row of the pass gets
 // an offset beyond the buffer, which the hardware answers with zeros WITHOUT touching memory -- a pass of M rows moves
 // M/32 of the fragment bytes (26/32 in a 26-node verify, 1/8 and less in the head's passes).
-template <int NWP, int NXP, int NR, int DEPTH>
+// Row-masked weight loads (half-block work split): the tiles of row block j come through a buffer resource over the
+// whole matrix; vo[j] is the lane's byte offset inside a tile, or an out-of-range offset for lanes whose weight row
+// is not this work-group's (zeros, no memory access); so[j] the byte offset of the block's first tile.
+struct FkHalf { __amdgpu_buffer_rsrc_t rs; uint32_t vo[4]; uint32_t so[4]; };
+
+template <int NWP, int NXP, int NR, int DEPTH, bool WB = false>
 __device__ __forceinline__ void fk_stream(const bf16_t* __restrict__ XF, int KS, int M, int kb, int ke, const u32x4* const* wp,
-                                          size_t wps, f32x16* acc, int lane) {
+                                          size_t wps, f32x16* acc, int lane, const FkHalf* hw = nullptr) {
+  static_assert(!WB || NWP == 1, "row-masked weight loads exist for one weight plane only");
   constexpr int PMAX = NWP > NXP ? NWP : NXP;
   if (ke <= kb) return;
   const int klast = ke - 1;
@@ -599,13 +605,17 @@ __device__ __forceinline__ void fk_stream(const bf16_t* __restrict__ XF, int KS,
   const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)XF, 0, NXP * KS * 1024, 0x00020000);
   const uint32_t xlane = (lane & 31) < M ? (uint32_t)lane * 16u : 0x80000000u;   // dead rows: out of range
 #define FK_XLOAD(q, kk) __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, (uint32_t)(((q) * KS + (kk)) * 1024), 0))
+  auto wload = [&](int j, int p, int kk) -> u32x4 {
+    if constexpr (WB) return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(hw->rs, hw->vo[j], hw->so[j] + (uint32_t)kk * 1024u, 0));
+    else return *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
+  };
 #pragma unroll
   for (int dd = 0; dd < DEPTH; ++dd) {
     const int kk = min(kb + dd, klast);
 #pragma unroll
     for (int j = 0; j < NR; ++j)
 #pragma unroll
-      for (int p = 0; p < NWP; ++p) ta[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kk * 64) + p * wps);
+      for (int p = 0; p < NWP; ++p) ta[dd][j][p] = wload(j, p, kk);
 #pragma unroll
     for (int q = 0; q < NXP; ++q) tb[dd][q] = FK_XLOAD(q, kk);
   }
@@ -626,7 +636,7 @@ __device__ __forceinline__ void fk_stream(const bf16_t* __restrict__ XF, int KS,
 #pragma unroll
       for (int j = 0; j < NR; ++j)
 #pragma unroll
-        for (int p = 0; p < NWP; ++p) ta[dd][j][p] = *(const u32x4*)((const bf16_t*)(wp[j] + (size_t)kn * 64) + p * wps);
+        for (int p = 0; p < NWP; ++p) ta[dd][j][p] = wload(j, p, kn);
 #pragma unroll
       for (int q = 0; q < NXP; ++q) tb[dd][q] = FK_XLOAD(q, kn);
       __builtin_amdgcn_sched_barrier(0);
@@ -648,12 +658,12 @@ __device__ __forceinline__ void fk_stream(const bf16_t* __restrict__ XF, int KS,
   }
 }
 #undef FK_XLOAD
-template <int NWP, int NXP, int NR>
+template <int NWP, int NXP, int NR, bool WB = false>
 __device__ __forceinline__ void fk_stream_dispatch(int nr, const bf16_t* XF, int KS, int M, int kb, int ke, const u32x4* const* wp,
-                                                   size_t wps, f32x16* acc, int lane) {
+                                                   size_t wps, f32x16* acc, int lane, const FkHalf* hw = nullptr) {
   constexpr int DEPTH = NWP == 1 ? (NR == 1 ? 8 : NR == 2 ? 6 : NR == 3 ? 5 : 4) : 2;   // ~24 KiB in flight per wave; deeper measured the same
-  if (nr == NR) fk_stream<NWP, NXP, NR, DEPTH>(XF, KS, M, kb, ke, wp, wps, acc, lane);
-  else if constexpr (NR > 1) fk_stream_dispatch<NWP, NXP, NR - 1>(nr, XF, KS, M, kb, ke, wp, wps, acc, lane);
+  if (nr == NR) fk_stream<NWP, NXP, NR, DEPTH, WB>(XF, KS, M, kb, ke, wp, wps, acc, lane, hw);
+  else if constexpr (NR > 1) fk_stream_dispatch<NWP, NXP, NR - 1, WB>(nr, XF, KS, M, kb, ke, wp, wps, acc, lane, hw);
 }
 
 // sum over the 8 waves of element (row n_local of row block j, token m) of the per-wave accumulators parked in LDS
@@ -666,7 +676,12 @@ __device__ inline float fk_sum(const float* red, int nrmax, int j, int n_local, 
   return a;
 }
 
-template <int NWP, int NXP, int NRMAX>
+// HALF: the unit of the work split is half a row block (16 weight rows) instead of a whole one, for matrices whose
+// row blocks do not divide evenly over the CUs (QKV at d = 4096: 384 blocks over 256 CUs = 1 or 2 each, but 3 halves
+// each).  A work-group then owns a run of halves; of a block it shares with a neighbour it loads and finishes only
+// its own 16 rows (the other lanes of the tile load nothing and multiply zeros).  Rotate-half pairs are adjacent rows,
+// so a half holds whole pairs; used for the QKV epilogue only.
+template <int NWP, int NXP, int NRMAX, bool HALF = false>
 __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sh_small[16 * 33];
@@ -677,12 +692,31 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
   unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
   if (tr) tr[0] = wall_clock64();
   const unsigned G = gridDim.x;
-  const int rb0 = (unsigned)blockIdx.x * (unsigned)g.NRB / G, rb1 = (unsigned)(blockIdx.x + 1) * (unsigned)g.NRB / G;
+  int rb0, rb1, row_lo = 0, row_hi = 32;                        // rows [row_lo, 32) of the first block, [0, row_hi) of the last
+  if constexpr (HALF) {
+    const unsigned U = 2u * (unsigned)g.NRB;
+    const unsigned u0 = (unsigned)blockIdx.x * U / G, u1 = (unsigned)(blockIdx.x + 1) * U / G;
+    rb0 = (int)(u0 >> 1); rb1 = (int)((u1 + 1) >> 1);
+    row_lo = (u0 & 1) ? 16 : 0; row_hi = (u1 & 1) ? 16 : 32;
+  } else {
+    rb0 = (unsigned)blockIdx.x * (unsigned)g.NRB / G; rb1 = (unsigned)(blockIdx.x + 1) * (unsigned)g.NRB / G;
+  }
   const int nr = rb1 - rb0;                                     // <= NRMAX (host)
   const int kb = (unsigned)w * (unsigned)g.KS / 8u, ke = (unsigned)(w + 1) * (unsigned)g.KS / 8u;
   const u32x4* wp[NRMAX];
 #pragma unroll
   for (int j = 0; j < NRMAX; ++j) wp[j] = (const u32x4*)(g.W + (size_t)min(rb0 + j, g.NRB - 1) * g.KS * 512) + lane;
+  FkHalf hw;
+  if constexpr (HALF) {
+    hw.rs = __builtin_amdgcn_make_buffer_rsrc((void*)g.W, 0, (int)((unsigned)g.NRB * (unsigned)g.KS * 1024u), 0x00020000);
+    const int row = lane & 31;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool mine = j < nr && row >= (j == 0 ? row_lo : 0) && row < (j == nr - 1 ? row_hi : 32);
+      hw.vo[j] = mine ? (uint32_t)lane * 16u : 0x80000000u;
+      hw.so[j] = (uint32_t)min(rb0 + j, g.NRB - 1) * (uint32_t)g.KS * 1024u;
+    }
+  }
   f32x16 acc[NRMAX];
 #pragma unroll
   for (int j = 0; j < NRMAX; ++j)
@@ -703,7 +737,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
       }
     }
   }
-  fk_stream_dispatch<NWP, NXP, NRMAX>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane);
+  fk_stream_dispatch<NWP, NXP, NRMAX, HALF>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane, &hw);
   if (tr) tr[2] = wall_clock64() + (acc[0][0] == 123.456f ? 1 : 0);
   // park every wave's sums in LDS
 #pragma unroll
@@ -735,6 +769,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
       const int j = it >> 4, pp = it & 15;
       const int n = (rb0 + j) * 32 + 2 * pp;
       if (n >= g.N || !live) continue;
+      if (HALF && (2 * pp < (j == 0 ? row_lo : 0) || 2 * pp >= (j == nr - 1 ? row_hi : 32))) continue;   // the neighbour's rows
       float a = fk_sum(red, NRMAX, j, 2 * pp, m) * rs, b = fk_sum(red, NRMAX, j, 2 * pp + 1, m) * rs;
       const int hd = n / dh, pr = n % dh;
       int d1, d2;
