@@ -10,6 +10,7 @@
 #include <cstring>
 #include <cstdlib>
 #include <vector>
+#include <algorithm>
 
 static thread_local char g_err[512] = "";
 static int fail(int code, const char* fmt, ...) {
@@ -1273,9 +1274,10 @@ extern "C" int eagle_set_profiling(eagle_ctx* c, int32_t mode) {
     HIPCHK(hipStreamSynchronize(c->stream));
     for (int i = 0; i <= n; ++i) HIPCHK(hipEventRecord(c->gemm_ev[i], c->stream));
     HIPCHK(hipStreamSynchronize(c->stream));
-    double tot = 0;
-    for (int i = 0; i < n; ++i) { float ms = 0.f; HIPCHK(hipEventElapsedTime(&ms, c->gemm_ev[i], c->gemm_ev[i + 1])); tot += ms; }
-    c->event_pair_ms = tot / n;
+    std::vector<float> gaps(n);                            // the median: a late first record or a stray stall must not move it
+    for (int i = 0; i < n; ++i) HIPCHK(hipEventElapsedTime(&gaps[i], c->gemm_ev[i], c->gemm_ev[i + 1]));
+    std::sort(gaps.begin(), gaps.end());
+    c->event_pair_ms = 0.5 * ((double)gaps[n / 2 - 1] + (double)gaps[n / 2]);
   }
   return EAGLE_OK;
 }
