@@ -261,6 +261,40 @@ def test_llama70b_twin_bf16_lockstep():
     assert toks[:52] == future[:52]
 
 
+@pytest.mark.parametrize("shape_name,n_layers", [("llama2-7b", 2), ("mini-moe", 2)])
+def test_repeated_runs_are_bitwise_identical(shape_name, n_layers):
+    """Every reduction on the path has a fixed order and every cross-work-group exchange is published before it is
+    read, so two runs of the same decode give the same bits: verify logits compared step by step over three runs
+    (hinted speculative decoding after the engine's own vanilla run), and the tokens equal the vanilla tokens."""
+    s = synth.SHAPES[shape_name].twin(n_layers)
+    par, rk = synth.TREES["T26" if shape_name != "mini-moe" else "T15"]
+    eng = pkg.Eagle(s, par, rk, max_seq=512)
+    eng.load_weights(synth.iter_weights(s, 7, synth.device_fmt(s)))
+    prompt = synth.prompt(7, 130, s.vocab)
+    steps = 12
+    fut = list(prompt) + [eng.prefill(0, prompt)]
+    for _ in range(steps * 6 + 8):
+        fut.append(int(eng.vanilla_step()[0]))
+    runs = []
+    for rep in range(3):
+        eng.reset()
+        eng.prefill(0, prompt)
+        eng.set_hint(0, fut, 0.7773, 30.0, 1234)
+        logits = []
+        for _ in range(steps):
+            eng.draft_tree()
+            eng.verify()
+            logits.append(eng.get_buffer(pkg.BUF_LOGITS, 0).copy())
+            eng.accept()
+        toks = list(eng.get_buffer(pkg.BUF_TOKENS, 0))
+        assert toks == fut[:len(toks)]
+        runs.append(logits)
+    for rep in (1, 2):
+        for a, b in zip(runs[0], runs[rep]):
+            assert np.array_equal(a, b)
+    eng.close()
+
+
 @pytest.mark.parametrize("tree,n_new", [("root", 10), ("chain5", 24), ("B63", 24)])
 def test_tiny_other_trees(tree, n_new):
     """Degenerate and large trees on the tiny fp32 model: a tree of the root alone (every step is a vanilla step and
