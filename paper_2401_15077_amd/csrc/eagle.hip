@@ -75,6 +75,8 @@ struct eagle_ctx {
   float *pend_f, *node_f, *F, *chunk_f, *featbuf;
   float *draft_logits, *L, *vanilla_logits, *pbuf, *qbuf, *gumbel;
   int *tree_tok, *on_path, *path, *tok_out, *len_out;
+  void* res_host = nullptr;          // pinned host copy of [path | tok_out | len_out]
+  ~eagle_ctx() { if (res_host) (void)hipHostFree(res_host); }
   // activations
   float *h, *Q, *PT, *part_o, *part_ml;
   bf16_t *xf_d, *xf_2d, *xf_att, *xf_ffn;
@@ -281,7 +283,7 @@ static size_t layout(eagle_ctx* c) {
   c->qbuf = a.take<float>((size_t)B * V);
   c->gumbel = a.take<float>(g.temperature > 0.f ? (size_t)B * std::max(1, c->max_level_rows) * V : 1);
   c->tree_tok = a.take<int>((size_t)B * M); c->on_path = a.take<int>((size_t)B * M);
-  c->path = a.take<int>((size_t)B * D1); c->tok_out = a.take<int>((size_t)B * D1); c->len_out = a.take<int>(B);
+  c->path = a.take<int>((size_t)B * D1); c->tok_out = a.take<int>((size_t)B * D1); c->len_out = a.take<int>(B);   // kept adjacent: fetched in one copy
   // activations
   const int Mm = c->Mmax, MTm = Mm / 32;
   c->h = a.take<float>((size_t)Mm * d);
@@ -389,6 +391,10 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   k_fill_u32<<<2048, 256, 0, c->stream>>>((uint32_t*)z0, 0u, zbytes / 4);
   if (hipGetLastError() != hipSuccess) { delete c; return fail(EAGLE_EHIP, "fill launch failed"); }
   if (hipMemcpyAsync(c->tree_d, &c->tree_h, sizeof(TreeDev), hipMemcpyHostToDevice, c->stream) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "tree upload failed"); }
+  {
+    const size_t span = (size_t)((const char*)(c->len_out + c->cfg.max_batch) - (const char*)c->path);
+    if (hipHostMalloc(&c->res_host, span, hipHostMallocDefault) != hipSuccess) { c->res_host = nullptr; delete c; return fail(EAGLE_ENOMEM, "pinned result buffer"); }
+  }
   // RoPE tables: angle = pos * theta^(-2i/dh) formed in fp64, rounded once to fp32
   {
     const int half = g.head_dim / 2;
@@ -1083,11 +1089,14 @@ static int do_accept(eagle_ctx* c) {
 
 static int fetch_results(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
   const int B = c->n_active, D1 = c->D + 1;
-  std::vector<int> len(B);
-  HIPCHK(hipMemcpyAsync(len.data(), c->len_out, (size_t)B * 4, hipMemcpyDeviceToHost, c->stream));
-  if (out_tokens) HIPCHK(hipMemcpyAsync(out_tokens, c->tok_out, (size_t)B * D1 * 4, hipMemcpyDeviceToHost, c->stream));
-  if (path) HIPCHK(hipMemcpyAsync(path, c->path, (size_t)B * D1 * 4, hipMemcpyDeviceToHost, c->stream));
+  // path, tokens and lengths lie next to each other in the workspace: one copy into pinned host memory brings all three
+  const size_t span = (size_t)((const char*)(c->len_out + c->cfg.max_batch) - (const char*)c->path);
+  HIPCHK(hipMemcpyAsync(c->res_host, c->path, span, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(hipStreamSynchronize(c->stream));
+  const char* rh = (const char*)c->res_host;
+  const int* len = (const int*)(rh + ((const char*)c->len_out - (const char*)c->path));
+  if (out_tokens) memcpy(out_tokens, rh + ((const char*)c->tok_out - (const char*)c->path), (size_t)B * D1 * 4);
+  if (path) memcpy(path, rh, (size_t)B * D1 * 4);
   for (int s = 0; s < B; ++s) {
     if (len[s] < 1 || len[s] > D1) return fail(EAGLE_EHIP, "internal: accepted length %d out of range", len[s]);
     c->h_ctx[s] += len[s]; c->h_ntok[s] += len[s];
