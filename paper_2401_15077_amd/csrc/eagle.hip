@@ -689,8 +689,8 @@ static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bo
   const eagle_config& g = c->cfg;
   const int M = pass.rows_per_seq * pass.n_seq, MT = (M + 31) / 32;
   int rc, S;
-  if (c->f32) k_fc_input<float><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
-  else k_fc_input<bf16_t><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
+  if (c->f32) k_fc_input<float><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
+  else k_fc_input<bf16_t><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
   LAUNCH_CHECK();
   if ((rc = gemm(c, c->fc, c->xf_2d, MT, &S))) return rc;
   const float* bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;
@@ -916,8 +916,8 @@ static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new)
   const eagle_config& cf = c->cfg;
   const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
   int rc;
-  if (c->f32) k_fc_input<float><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
-  else k_fc_input<bf16_t><<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
+  if (c->f32) k_fc_input<float><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
+  else k_fc_input<bf16_t><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf2_2d, d, cf.vocab, 1, c->NXP);
   LAUNCH_CHECK();
   Gemm2 g = gemm2_base(c, pass, M);
   g.epi = EPI_RESID; g.h_in = nullptr; g.h_out = c->h2; g.bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;

@@ -364,7 +364,8 @@ __global__ __launch_bounds__(256) void k_fc_input(Pass pass, const TreeDev* tree
     }
   }
   tok = min(max(tok, 0), vocab - 1);
-  for (int k8 = threadIdx.x * 8; k8 < 2 * d; k8 += blockDim.x * 8) {
+  // blockIdx.y splits the 2d columns so that a pass of a few rows still spreads over many CUs
+  for (int k8 = (blockIdx.y * blockDim.x + threadIdx.x) * 8; k8 < 2 * d; k8 += gridDim.y * blockDim.x * 8) {
     float x[8];
     for (int t = 0; t < 8; ++t) {
       int k = k8 + t;
