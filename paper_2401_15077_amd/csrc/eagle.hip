@@ -74,7 +74,7 @@ struct eagle_ctx {
   int *hint_future, *hint_n; float *hint_alpha, *hint_bias; unsigned long long* hint_seed;
   float *pend_f, *node_f, *F, *chunk_f, *featbuf;
   float *draft_logits, *L, *vanilla_logits, *pbuf, *qbuf, *gumbel;
-  int *tree_tok, *on_path, *path, *tok_out, *len_out;
+  int *tree_tok, *on_path, *path, *tok_out, *len_out, *row_amax;
   void* res_host = nullptr;          // pinned host copy of [path | tok_out | len_out]
   ~eagle_ctx() { if (res_host) (void)hipHostFree(res_host); }
   // activations
@@ -282,7 +282,7 @@ static size_t layout(eagle_ctx* c) {
   c->pbuf = a.take<float>((size_t)B * V);
   c->qbuf = a.take<float>((size_t)B * V);
   c->gumbel = a.take<float>(g.temperature > 0.f ? (size_t)B * std::max(1, c->max_level_rows) * V : 1);
-  c->tree_tok = a.take<int>((size_t)B * M); c->on_path = a.take<int>((size_t)B * M);
+  c->tree_tok = a.take<int>((size_t)B * M); c->on_path = a.take<int>((size_t)B * M); c->row_amax = a.take<int>((size_t)B * M);
   c->path = a.take<int>((size_t)B * D1); c->tok_out = a.take<int>((size_t)B * D1); c->len_out = a.take<int>(B);   // kept adjacent: fetched in one copy
   // activations
   const int Mm = c->Mmax, MTm = Mm / 32;
@@ -1076,7 +1076,8 @@ static int do_accept(eagle_ctx* c) {
   if (c->phase != 2) return fail(EAGLE_ESTATE, "eagle_accept needs verified logits (call eagle_verify first)");
   const eagle_config& g = c->cfg;
   const int B = c->n_active;
-  k_accept<<<B, 1024, 0, c->stream>>>(c->tree_d, c->st, c->L, c->draft_logits, c->tree_tok, g.vocab, g.temperature, g.seed, c->pbuf, c->qbuf, c->path, c->tok_out, c->len_out);
+  if (g.temperature <= 0.f) { k_row_argmax<<<B * c->M, 1024, 0, c->stream>>>(c->L, g.vocab, c->row_amax); LAUNCH_CHECK(); }
+  k_accept<<<B, 1024, 0, c->stream>>>(c->tree_d, c->st, c->L, c->draft_logits, c->tree_tok, g.vocab, g.temperature, g.seed, c->pbuf, c->qbuf, c->path, c->tok_out, c->len_out, c->row_amax);
   LAUNCH_CHECK();
   dim3 grid(4, g.n_layers + 1, B);
   KVCache kv = kv_for(c, 0);

@@ -786,10 +786,23 @@ __global__ __launch_bounds__(1024) void k_choose(SeqState st, int seq0, const fl
 //   T > 0  : children in rank order, accept child i when r * q_i(t_i) < p(t_i); on rejection
 //            p <- norm(max(0, p - q_i)) and q_{i+1} = q_i without t_i, renormalised (children were drawn
 //            without replacement); when nothing is accepted draw the bonus token from what is left of p.
+// arg-max token of every row of logits (lowest id among equals), one block per row: the greedy walk below visits up
+// to depth + 1 nodes one after the other, and scanning their rows there would run on a single CU
+__global__ __launch_bounds__(1024) void k_row_argmax(const float* __restrict__ L, int V, int* __restrict__ amax) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
+  const float* lg = L + (size_t)blockIdx.x * V;
+  float bv = -INFINITY; int bi = 0x7fffffff;
+  for (int j = threadIdx.x; j < V; j += blockDim.x) better(bv, bi, lg[j], j);
+  block_argmax(bv, bi, shv, shi);
+  if (threadIdx.x == 0) amax[blockIdx.x] = bi;
+}
+
 __global__ __launch_bounds__(1024) void k_accept(const TreeDev* tree, SeqState st, const float* L /*[seq][M][V]*/,
                                                  const float* draft_logits, const int* tree_tok, int V, float temperature,
                                                  unsigned long long rng_seed, float* pbuf, float* qbuf,
-                                                 int* path_out /*[seq][D+1]*/, int* tok_out, int* len_out) {
+                                                 int* path_out /*[seq][D+1]*/, int* tok_out, int* len_out,
+                                                 const int* __restrict__ amax /*[seq][M], greedy only*/) {
   __shared__ float shv[16];
   __shared__ int shi[16];
   __shared__ float sh_f[1025];
@@ -802,9 +815,7 @@ __global__ __launch_bounds__(1024) void k_accept(const TreeDev* tree, SeqState s
     const float* lg = L + ((size_t)seq * M + cur) * V;
     const int nk = tree->nchild[cur];
     if (temperature <= 0.f) {
-      float bv = -INFINITY; int bi = 0x7fffffff;
-      for (int j = threadIdx.x; j < V; j += blockDim.x) better(bv, bi, lg[j], j);
-      block_argmax(bv, bi, shv, shi);
+      const int bi = amax[seq * M + cur];
       if (threadIdx.x == 0) {
         s_next = -1;
         for (int r = 0; r < nk; ++r) {
