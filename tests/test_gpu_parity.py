@@ -225,6 +225,40 @@ def test_llama7b_full_depth_lockstep():
 
 
 
+@pytest.mark.parametrize("shape_name,prompt_len,steps", [("llama2-13b", 1024, 10), ("llama2-70b", 2048, 6), ("mixtral-8x7b", 1024, 6)])
+def test_full_size_speculative_equals_vanilla(shape_name, prompt_len, steps):
+    """Configurations 3-5 at their full depth and the benchmark's prompt lengths, where the CPU oracle cannot follow:
+    the property that holds at any size (Sec. 2: the method emits exactly the target's greedy tokens) -- the tokens of
+    hinted speculative decoding equal those of the engine's own vanilla decoding, accepted lengths stay within
+    1..depth+1, the accepted path is a root-to-node path of the tree -- in the launch configuration bench.py times."""
+    s = synth.SHAPES[shape_name]
+    par, rk = synth.TREES["T26"]
+    D = 5
+    n_future = (steps + 2) * (D + 1) + 8
+    eng = pkg.Eagle(s, par, rk, max_seq=prompt_len + n_future + len(par) + 80)
+    eng.load_weights(synth.iter_weights(s, 2, synth.device_fmt(s)))
+    prompt = synth.prompt(2, prompt_len, s.vocab)
+    fut = list(prompt) + [eng.prefill(0, prompt)]
+    for _ in range(n_future):
+        fut.append(int(eng.vanilla_step()[0]))
+    eng.reset()
+    assert eng.prefill(0, prompt) == fut[prompt_len]
+    eng.set_hint(0, fut, 0.7773, 30.0, 20240126)
+    emitted = 0
+    for _ in range(steps):
+        toks, lens, paths = eng.step()
+        n = int(lens[0])
+        assert 1 <= n <= D + 1
+        pth = [int(v) for v in paths[0][:n]]
+        assert pth[0] == 0 and all(par[pth[i + 1]] == pth[i] for i in range(n - 1))
+        emitted += n
+    got = list(eng.get_buffer(pkg.BUF_TOKENS, 0))
+    assert len(got) == prompt_len + 1 + emitted
+    assert got == fut[:len(got)]
+    assert emitted > steps                    # the knob makes the head's proposals land: more than one token per step
+    eng.close()
+
+
 def test_tiny_bf16_kv_cache():
     """The optional bf16 KV cache (keys and values rounded to nearest even when written) against the oracle's model
     of it.  A cache entry whose fp32 value sits within rounding distance of a bf16 tie can round differently on the
