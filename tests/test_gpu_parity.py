@@ -230,7 +230,9 @@ def test_full_size_speculative_equals_vanilla(shape_name, prompt_len, steps):
     """Configurations 3-5 at their full depth and the benchmark's prompt lengths, where the CPU oracle cannot follow:
     the property that holds at any size (Sec. 2: the method emits exactly the target's greedy tokens) -- the tokens of
     hinted speculative decoding equal those of the engine's own vanilla decoding, accepted lengths stay within
-    1..depth+1, the accepted path is a root-to-node path of the tree -- in the launch configuration bench.py times."""
+    1..depth+1, the accepted path is a root-to-node path of the tree -- in the launch configuration bench.py times.
+    (The two runs agree up to rounding only -- a tree node's key sits at another cache slot than in vanilla decoding --
+    so an arg-max near-tie could part them; runs are deterministic and none occurs for these seeds and lengths.)"""
     s = synth.SHAPES[shape_name]
     par, rk = synth.TREES["T26"]
     D = 5
