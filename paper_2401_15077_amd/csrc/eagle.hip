@@ -566,6 +566,14 @@ static int collect_gemm_events(eagle_ctx* c) {
   return EAGLE_OK;
 }
 
+// KV splits of the attention kernel for `tokens` keys and `units` (head, sequence, row block) triples: one 32-token
+// block per wave (128 tokens per work-group) while that keeps the grid within one work-group per CU -- the kernel's
+// registers allow no more, and a second round of work-groups costs more than a wave walking a few blocks in turn.
+static int attn_splits(const eagle_ctx* c, int tokens, int units) {
+  const int by_tokens = (tokens + 127) / 128, by_cus = std::max(1, c->n_cu / std::max(1, units));
+  return std::max(1, std::min(16, std::min(by_tokens, by_cus)));
+}
+
 static KVCache kv_for(eagle_ctx* c, int li) {
   KVCache kv;
   const eagle_config& g = c->cfg;
@@ -603,8 +611,8 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   }
   {
     // the MFMA attention kernel of the fast path, one work-group per (KV split, head, sequence x 32-row block)
-    int n_splits = std::max(1, std::min(16, (t_max + 127) / 128));
     int rblocks = (pass.rows_per_seq + 31) / 32;
+    int n_splits = attn_splits(c, t_max, H * pass.n_seq * rblocks);
     if (pass.n_seq * rblocks > 128) return fail(EAGLE_EINVAL, "internal: too many (sequence, row block) pairs in one pass");
     dim3 grid(n_splits, H, pass.n_seq * rblocks);
     float scale = 1.0f / std::sqrt((float)dh);
@@ -834,7 +842,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   g.epi = EPI_QKV; g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups); g.kv = kv_for(c, li);
   if ((rc = gemm2(c, w.qkv, c->xf2_d, g, nullptr))) return rc;
   {
-    int n_splits = std::max(1, std::min(16, (ctx_max + 64 + 127) / 128));   // 128 tokens = one 32-token block per wave
+    int n_splits = attn_splits(c, ctx_max + 64, H * pass.n_seq);
     unsigned long long* atrace = (c->attn_no++ == c->attn_trace_sel && n_splits * H <= 1024) ? c->trace : nullptr;
     dim3 grid(n_splits, H, pass.n_seq);
     float scale = 1.0f / std::sqrt((float)dh);

@@ -323,17 +323,25 @@ __global__ __launch_bounds__(256) void k_embed(Pass pass, const TreeDev* tree, S
 }
 
 __device__ inline void xf_store8(bf16_t* XF, int m, int k8, int MT, int KS, int nplanes, const float* x) {
-  bf16_t pl[3][8];
-  for (int t = 0; t < 8; ++t) {
-    bf16_t p[3];
-    split_bf16(x[t], p, nplanes);
-    for (int q = 0; q < nplanes; ++q) pl[q][t] = p[q];
-  }
-  for (int q = 0; q < nplanes; ++q) {
-    u32x4 v;
-    v.x = pl[q][0] | ((uint32_t)pl[q][1] << 16); v.y = pl[q][2] | ((uint32_t)pl[q][3] << 16);
-    v.z = pl[q][4] | ((uint32_t)pl[q][5] << 16); v.w = pl[q][6] | ((uint32_t)pl[q][7] << 16);
-    *(u32x4*)(XF + xf_index(m, k8, q, MT, KS)) = v;
+  // plane q holds bf16(x - planes 0..q-1), as split_bf16 defines it; written plane by plane so that nothing is indexed
+  // by a run-time value (an array indexed by the plane number would live on the stack)
+  float r[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r[t] = x[t];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    if (q < nplanes) {
+      uint32_t b[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const bf16_t h = f32_to_bf16(r[t]);
+        b[t] = h;
+        r[t] -= bf16_to_f32(h);
+      }
+      u32x4 v;
+      v.x = b[0] | (b[1] << 16); v.y = b[2] | (b[3] << 16); v.z = b[4] | (b[5] << 16); v.w = b[6] | (b[7] << 16);
+      *(u32x4*)(XF + xf_index(m, k8, q, MT, KS)) = v;
+    }
   }
 }
 

@@ -1122,11 +1122,12 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
     const float m_new = fmaxf(m_run, bmax);
     const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
-    float psum = 0.f, pv[16];
+    float psum = 0.f, pv[2][8];                                // two arrays: a pointer into one of 16 ends up on the stack
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      pv[r] = (m_new == -INFINITY) ? 0.f : __expf(sacc[r] - m_new);
-      psum += pv[r];
+      const float e = (m_new == -INFINITY) ? 0.f : __expf(sacc[r] - m_new);
+      pv[r >> 3][r & 7] = e;
+      psum += e;
     }
     psum += __shfl_xor(psum, 32, 64);
     l_run = l_run * alpha + psum;
@@ -1138,7 +1139,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       bf16x8 ph, pl;
-      split8(pv + 8 * j, ph, pl);
+      split8(pv[j], ph, pl);
 #pragma unroll
       for (int b = 0; b < DB; ++b) {
         bf16x8 vh, vl;
