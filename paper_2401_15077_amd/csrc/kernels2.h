@@ -1048,9 +1048,11 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     const RowInfo ri = row_info(pass, tree, st, r0 + q);
     rel = ri.rel; causal = ri.causal; mask = ri.mask;
   }
-  bf16x8 qh[KSN], ql[KSN];
-#pragma unroll
-  for (int ks = 0; ks < KSN; ++ks) {
+  // The scaled queries as bf16 hi + lo B-operand fragments live in LDS, built once by the four waves together (wave w
+  // converts k-steps w, w+4, ...); they share the memory of o_s, which is not written before every wave has left the
+  // key loop.  (One load and one conversion of the queries per work-group instead of one per wave.)
+  bf16x8* q_s = (bf16x8*)smem_a;                               // [2 planes][KSN][64 lanes]
+  for (int ks = w; ks < KSN; ks += 4) {
     float x[8];
     if (q < R) {
       load8(Q + ((size_t)(r0 + q) * H + hd) * DH + 16 * ks + 8 * hh, x);
@@ -1060,8 +1062,12 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
       for (int t = 0; t < 8; ++t) x[t] = 0.f;
     }
-    split8(x, qh[ks], ql[ks]);
+    bf16x8 h8, l8;
+    split8(x, h8, l8);
+    q_s[(0 * KSN + ks) * 64 + lane] = h8;
+    q_s[(1 * KSN + ks) * 64 + lane] = l8;
   }
+  __syncthreads();
   const int T = base + n_new;
   // the split boundaries depend on `base` only, so a row sees the same partition whatever else is in the pass
   const int span = base + max(64, (n_new + 63) / 64 * 64);   // passes with at most 64 new rows share one partition
@@ -1089,9 +1095,10 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     for (int ks = 0; ks < KSN; ++ks) {
       bf16x8 kh, kl;
       split8(kx[ks], kh, kl);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[ks], sacc, 0, 0, 0);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[ks], sacc, 0, 0, 0);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[ks], sacc, 0, 0, 0);
+      const bf16x8 qh = q_s[(0 * KSN + ks) * 64 + lane], ql = q_s[(1 * KSN + ks) * 64 + lane];
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh, sacc, 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql, sacc, 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh, sacc, 0, 0, 0);
     }
     // V gathers go out before the softmax arithmetic: slot t of lane-half hh in k-step j is the token that
     // accumulator register 8j+t of the same lane-half holds
@@ -1151,6 +1158,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     }
   }
   if (tr) tr[1] = wall_clock64();
+  __syncthreads();                          // every wave is done with the query fragments that o_s overlays
   // merge the 4 waves through LDS: o_s[w][d][q], d = 32b + 8(r/4) + 4hh + r%4
 #pragma unroll
   for (int b = 0; b < DB; ++b)
