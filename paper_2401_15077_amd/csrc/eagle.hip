@@ -114,8 +114,6 @@ static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
   return p;
 }
 
-// Work split of the fast-path GEMM: S K-slices x `groups` row groups = one work-group each; inside a work-group
-// `lanes` x `kparts` waves (product 8): a wave owns every lanes-th row block of the group over one k-part.
 // Work split of the split-K kernel with streamed activations: S slices x groups of at most 4 row blocks, chosen by a
 // fetch model in KiB per work-group (weights + the live part of the X slice + twice the partials the last work-group
 // of a row group reads back, which sit on the critical path of one CU).  Depends on the matrix shape only.
@@ -133,6 +131,8 @@ static PlanXK plan_xk(int NRB, int KS, int NXP, int n_cu, size_t pt_floats_per_s
   return best;
 }
 
+// Work split of the LDS-staged split-K kernel: S K-slices x `groups` row groups = one work-group each; inside a
+// work-group `lanes` x `kparts` waves (product 8): a wave owns every lanes-th row block of the group over one k-part.
 struct Plan2 { int S, groups, lanes, kparts, RW, kt_max; size_t lds; };
 static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
   Plan2 p;
