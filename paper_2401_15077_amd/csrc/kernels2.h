@@ -1080,14 +1080,25 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[b][r] = 0.f;
 
-  for (int tok0 = t_begin + 32 * w; tok0 < t_end; tok0 += 128) {   // wave w takes every 4th 32-token block
-    // a 32-token block starts on a multiple of 32 and therefore lies inside one 64-token (or larger) page
-    const size_t blk = kv_offset(kv, seq, tok0, kvh);
-    const CT* kp = (const CT*)kv.k + blk + (size_t)(lane & 31) * DH + 8 * hh;
-    const CT* vp = (const CT*)kv.v + blk;
-    float kx[KSN][8];
+  // Wave w takes every 4th 32-token block.  A block starts on a multiple of 32 and therefore lies inside one 64-token
+  // (or larger) page.  The keys of the NEXT block are requested as soon as the scores of the current one are done
+  // (the registers are free then), after the current block's values, so that they travel while the softmax and the
+  // P V product run: a wave that walks several blocks pays about one memory round trip per block.
+  float kx[KSN][8];
+  size_t blk = 0;
+  {
+    const int tok0 = t_begin + 32 * w;
+    if (tok0 < t_end) {
+      blk = kv_offset(kv, seq, tok0, kvh);
+      const CT* kp = (const CT*)kv.k + blk + (size_t)(lane & 31) * DH + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < KSN; ++ks) load8(kp + 16 * ks, kx[ks]);
+      for (int ks = 0; ks < KSN; ++ks) load8(kp + 16 * ks, kx[ks]);
+    }
+  }
+  for (int tok0 = t_begin + 32 * w; tok0 < t_end; tok0 += 128) {
+    const CT* vp = (const CT*)kv.v + blk;
+    const bool more = tok0 + 128 < t_end;
+    const size_t blk_next = more ? kv_offset(kv, seq, tok0 + 128, kvh) : 0;   // look-up in flight during the scores
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
@@ -1112,6 +1123,12 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
           const int tl = 16 * j + 8 * (t >> 2) + 4 * hh + (t & 3);
           vx[j][b][t] = cache_load(vp + (size_t)tl * DH + 32 * b + (lane & 31));
         }
+    if (more) {
+      const CT* kp = (const CT*)kv.k + blk_next + (size_t)(lane & 31) * DH + 8 * hh;
+#pragma unroll
+      for (int ks = 0; ks < KSN; ++ks) load8(kp + 16 * ks, kx[ks]);
+    }
+    blk = blk_next;
     // mask, running max and sum for this lane's query
     float bmax = -INFINITY;
 #pragma unroll
