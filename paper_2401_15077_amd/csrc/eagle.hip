@@ -920,7 +920,7 @@ static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_ne
   return lm_head2(c, pass, M, true, logits_out, out_kind, 0);
 }
 
-static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new) {
+static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, bool store_rows = true) {
   const eagle_config& cf = c->cfg;
   const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
   int rc;
@@ -932,8 +932,10 @@ static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new)
   g.gain_next = c->layers[cf.n_layers].attn_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
   if ((rc = gemm2(c, c->fc, c->xf2_2d, g, &c->ssq2_groups))) return rc;
   if ((rc = layer2(c, pass, M, cf.n_layers, ctx_max, n_new, nullptr))) return rc;
-  k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->h2, c->node_f, c->pend_f, c->chunk_f, d);
-  LAUNCH_CHECK();
+  if (store_rows) {                          // (the draft passes leave this copy to k_expand)
+    k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->h2, c->node_f, c->pend_f, c->chunk_f, d);
+    LAUNCH_CHECK();
+  }
   return lm_head2(c, pass, M, false, c->draft_logits, 0, 0);
 }
 
@@ -1041,20 +1043,24 @@ static int do_draft(eagle_ctx* c) {
   const eagle_config& g = c->cfg;
   Pass p1{PASS_DRAFT_PENDING, D1, B, 0, 0, 0, 0};
   pass_ctx(c, p1);
-  if ((rc = (D1 * B <= 32 ? head_forward2(c, p1, ctx, D1) : head_forward(c, p1, ctx + D1, D1, true)))) return rc;
+  const bool fast1 = D1 * B <= 32;
+  if ((rc = (fast1 ? head_forward2(c, p1, ctx, D1, false) : head_forward(c, p1, ctx + D1, D1, true)))) return rc;
   dim3 g0(1, B);
-  if (g.vocab > 32768) k_expand<true><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
-  else k_expand<false><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, getenv("EAGLE_EXPAND_TRACE") ? c->trace : nullptr);
+  const float* src1 = fast1 ? c->h2 : nullptr;   // fast path: k_expand stores the root's head feature itself
+  if (g.vocab > 32768) k_expand<true><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, src1, c->node_f, g.d_model, D1);
+  else k_expand<false><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, getenv("EAGLE_EXPAND_TRACE") ? c->trace : nullptr, src1, c->node_f, g.d_model, D1);
   LAUNCH_CHECK();
   for (int lev = 1; lev < c->D; ++lev) {
     int nr = c->tree_h.n_level_rows[lev];
     if (nr == 0) break;
     Pass pl{PASS_DRAFT_LEVEL, nr, B, 0, lev, 0, 0};
     pass_ctx(c, pl);
-    if ((rc = (nr * B <= 32 ? head_forward2(c, pl, ctx, c->M) : head_forward(c, pl, ctx + c->M, c->M, true)))) return rc;
+    const bool fastl = nr * B <= 32;
+    if ((rc = (fastl ? head_forward2(c, pl, ctx, c->M, false) : head_forward(c, pl, ctx + c->M, c->M, true)))) return rc;
     dim3 gl(nr, B);
-    if (g.vocab > 32768) k_expand<true><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
-    else k_expand<false><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr);
+    const float* srcl = fastl ? c->h2 : nullptr;
+    if (g.vocab > 32768) k_expand<true><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, srcl, c->node_f, g.d_model, nr);
+    else k_expand<false><<<gl, 1024, 0, c->stream>>>(lev, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, srcl, c->node_f, g.d_model, nr);
     LAUNCH_CHECK();
   }
   c->phase = 1;

@@ -566,7 +566,9 @@ struct HintDev {
 template <bool BIGV>   // BIGV: more than 32768 vocabulary entries (the scores of a row do not fit the block's registers)
 __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_seq, const TreeDev* tree, SeqState st,
                                                  float* draft_logits /*[seq][M][V]*/, int* tree_tok, int* on_path, HintDev hint,
-                                                 int V, float temperature, unsigned long long rng_seed, unsigned long long* trace) {
+                                                 int V, float temperature, unsigned long long rng_seed, unsigned long long* trace,
+                                                 const float* __restrict__ feat_src /*[pass rows][d] or null*/, float* node_f /*[seq][M][d]*/,
+                                                 int d, int src_rows_per_seq) {
   __shared__ float shv[16];
   __shared__ int shi[16];
   const int seq = blockIdx.y;
@@ -574,6 +576,16 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
   if (tr) tr[0] = wall_clock64();
   const int v = level < 0 ? 0 : tree->level_rows[level][blockIdx.x];
   const int M = tree->M;
+  // The node's own head feature (the row of the pass that produced these logits) goes to node_f here when the caller
+  // asks for it: one block per row of the pass exists anyway, which saves a separate copy kernel per pass.
+  // Row of the pass: a level pass lists the level's parent nodes in order; in a pending pass the root is the
+  // sequence's last pending row.
+  if (feat_src) {
+    const int row = seq * src_rows_per_seq + (level < 0 ? max(st.n_pend[seq] - 1, 0) : (int)blockIdx.x);
+    const float* src = feat_src + (size_t)row * d;
+    float* dst = node_f + ((size_t)seq * M + v) * d;
+    for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = src[k];
+  }
   float* lg = draft_logits + ((size_t)seq * M + v) * V;
   // Loads are grouped by what they depend on, so that the kernel pays two memory round trips, not one per fact:
   // (1) everything addressed by (seq, v) alone, including the first 32 logits of every thread ...
