@@ -50,6 +50,7 @@ def main() -> int:
     ap.add_argument("--tree", default="T26")
     ap.add_argument("--alpha", type=float, default=None, help="per-position hit probability of the knob (default: solved from --tau for this tree depth)")
     ap.add_argument("--seed", type=int, default=2)
+    ap.add_argument("--kv-dtype", default="fp32", choices=["fp32", "bf16"], help="storage type of the KV cache (the default, fp32, is what the parity tests of the bf16 configurations use)")
     ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (each with its own prompt and knob)")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic tree acceptance, no knob (natural acceptance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -79,7 +80,7 @@ def main() -> int:
     B = args.batch
     stochastic = args.temperature > 0.0
     t0 = time.time()
-    eng = pkg.Eagle(shape, par, rk, max_batch=B, max_seq=max_seq, temperature=args.temperature, seed=args.seed)
+    eng = pkg.Eagle(shape, par, rk, max_batch=B, max_seq=max_seq, temperature=args.temperature, seed=args.seed, kv_dtype=args.kv_dtype)
     eng.load_weights(synth.iter_weights(shape, args.seed, synth.device_fmt(shape)))
     t_load = time.time() - t0
     prompts = [synth.prompt(args.seed + 1000 * b, args.prompt, shape.vocab) for b in range(B)]
