@@ -57,8 +57,8 @@ typedef struct {
 } eagle_config;
 
 /* Which tensor eagle_load_weight() is given.  Matrices are row-major [out_features, in_features] in the
- * model dtype; norm gains and the FC bias are fp32 vectors.  MoE expert matrices are [n_experts, out, in],
- * the router is an fp32-or-model-dtype [n_experts, d_model] matrix in the model dtype. */
+ * model dtype; norm gains and the FC bias are fp32 vectors.  MoE expert matrices are [n_experts, out, in]; the
+ * router is an [n_experts, d_model] matrix in the model dtype (the library keeps and applies it in fp32). */
 enum {
   EAGLE_W_EMBED = 0, EAGLE_W_LM_HEAD, EAGLE_W_FINAL_NORM, EAGLE_W_FC, EAGLE_W_FC_BIAS,
   EAGLE_W_ATTN_NORM, EAGLE_W_Q, EAGLE_W_K, EAGLE_W_V, EAGLE_W_O, EAGLE_W_MLP_NORM, EAGLE_W_ROUTER,
@@ -120,6 +120,34 @@ int eagle_generate(eagle_ctx *ctx, int32_t seq, const int32_t *prompt_host, int3
  * future token gets +bias when hash(seed, index) < alpha and -bias otherwise.  n = 0 switches it off. */
 int eagle_set_hint(eagle_ctx *ctx, int32_t seq, const int32_t *future_host, int32_t n, float alpha, float bias, uint64_t seed);
 
+/* ---- Injection: lock-step tests and callers that bring their own decisions -------------------------------------
+ * These calls let the CPU side of a lock-step comparison drive the engine along ITS choices (Sec. 3.1 / App. A.1
+ * tree, Sec. 3.3 / App. A.2 acceptance), and let the child-selection and acceptance kernels be run on logits the
+ * caller supplies.  All of them synchronise the stream. */
+
+/* KV paging: physical page of every (slot, logical page), host int32[max_batch * pages_per_slot] with
+ * pages_per_slot = ceil(max_seq / page_tokens); must be a permutation of 0..max_batch*pages_per_slot-1.  Allowed only
+ * while no slot is active (EAGLE_ESTATE otherwise).  The default is the interleaved map page*max_batch + slot. */
+int eagle_set_page_table(eagle_ctx *ctx, const int32_t *table_host);
+
+/* Overwrite a context-owned buffer of slot `seq` from host memory: EAGLE_BUF_LOGITS, _FEATURES, _DRAFT_LOGITS,
+ * _DRAFT_FEATURES or _TREE_TOKENS; `bytes` must be the buffer's full size (see the enum below). */
+int eagle_set_buffer(eagle_ctx *ctx, int32_t which, int32_t seq, const void *host_src, size_t bytes);
+
+/* Replace the tokens of slot `seq`'s drafted tree (host int32[n_nodes], node 0 = the root token) between
+ * eagle_draft_tree and eagle_verify.  The knob's on-path flags are not recomputed. */
+int eagle_force_tree(eagle_ctx *ctx, int32_t seq, const int32_t *tokens_host);
+
+/* Child selection alone (App. A.1): the children of the nodes of tree level `level` (-1 = the root, else
+ * 1..depth-1: the level's nodes that have children) are chosen from whatever EAGLE_BUF_DRAFT_LOGITS holds --
+ * top-k when greedy, Gumbel top-k with the context's seed and draw counter otherwise -- for every active slot. */
+int eagle_expand_level(eagle_ctx *ctx, int32_t level);
+
+/* Commit given paths instead of running the acceptance rule, then compact as eagle_accept does.  Host arrays:
+ * path int32[n_active * (depth+1)] (node indices, path[0] = 0, each node a child of its predecessor),
+ * len int32[n_active] (1..depth+1 tokens emitted: len-1 accepted drafts + the bonus), bonus int32[n_active]. */
+int eagle_force_accept(eagle_ctx *ctx, const int32_t *path_host, const int32_t *len_host, const int32_t *bonus_host);
+
 /* Test / bench access to context-owned buffers (synchronises). `which`: */
 enum {
   EAGLE_BUF_LOGITS = 0,        /* fp32 [n_nodes, vocab]     verify logits of slot seq                      */
@@ -131,11 +159,12 @@ enum {
   EAGLE_BUF_VANILLA_LOGITS,    /* fp32 [vocab]              logits of the last eagle_vanilla_step / prefill */
   EAGLE_BUF_STATE,             /* int32 [4]: committed tokens, cached target positions, pending features, steps */
   EAGLE_BUF_KV_ROW,            /* see eagle_get_kv_row                                                      */
-  EAGLE_BUF_GEMM_TRACE         /* uint64 [1024 work-groups][8 events]: 100 MHz time stamps of ONE launch of the
+  EAGLE_BUF_GEMM_TRACE         /* profiling builds of the library (-DEAGLE_TRACE) only, all zero otherwise:
+                                  uint64 [1024 work-groups][8 events], 100 MHz time stamps of ONE launch of the
                                   weight-streaming GEMM kernel, selected with the environment variable
                                   EAGLE_GEMM_TRACE=<index of the launch within the verify phase> (read by eagle_init);
                                   events: 0 entered, 1 activations staged, 2 weight stream done, 3 partial sums
-                                  published, 4 epilogue done (the work-groups that ran one).  Zero where unset. */
+                                  published, 4 epilogue done (the work-groups that ran one). */
 };
 int eagle_get_buffer(eagle_ctx *ctx, int32_t which, int32_t seq, void *host_dst, size_t cap_bytes);
 /* K and V (fp32, [n_kv_heads*head_dim] each) of target layer `layer` (or EAGLE_HEAD_LAYER) at cache position pos. */

@@ -192,9 +192,11 @@ def drop_and_renorm(q: np.ndarray, t: int) -> np.ndarray:
 
 
 def sample_inverse_cdf(p: np.ndarray, u: float) -> int:
-    """Smallest x with cumsum(p)[x] > u * sum(p)."""
-    c = np.cumsum(p)
-    x = int(np.searchsorted(c, np.asarray(u, dtype=p.dtype) * c[-1], side="right"))
+    """Smallest x with cumsum(p)[x] > u * sum(p).  The running sum is ALWAYS carried in fp64, whatever p's dtype: a
+    vocabulary of 32000 entries has bins of ~3e-5, which an fp32 running sum (error ~1e-5) cannot resolve, so the
+    draw would depend on the order of the additions instead of on p."""
+    c = np.cumsum(p, dtype=np.float64)
+    x = int(np.searchsorted(c, float(u) * c[-1], side="right"))
     return min(x, p.size - 1)
 
 
@@ -318,8 +320,12 @@ class Oracle:
 
     @staticmethod
     def _cdf_margin(p: np.ndarray, u: float) -> float:
-        c = np.cumsum(p)
-        return float(np.min(np.abs(c - u * c[-1])))
+        """Distance of the drawn point to the nearest boundary of the drawn token's bin, relative to the bin's width."""
+        c = np.cumsum(p, dtype=np.float64)
+        target = float(u) * c[-1]
+        x = min(int(np.searchsorted(c, target, side="right")), p.size - 1)
+        lo = c[x - 1] if x > 0 else 0.0
+        return float(min(target - lo, c[x] - target) / max(float(p[x]), 1e-300))
 
     # -- life cycle ---------------------------------------------------------------------------------
     @property
@@ -334,7 +340,7 @@ class Oracle:
         F, L = self._target_forward(prompt, pos, pos, causal, "prefill")
         self.prefill_features, self.prefill_logits = F, L
         self.step = 0                                     # the first token is draw number 0
-        first, _ = self._choose(L[P - 1], 0)
+        first, self.first_margin = self._choose(L[P - 1], 0)
         self.x = [int(t) for t in prompt] + [first]
         if P > 1:   # draft rows 0..P-2: (f[i], x[i+1])
             self._head_forward(F[:P - 1], self.x[1:P], pos[:P - 1], pos[:P - 1], causal[:P - 1, :P - 1], "dprefill")

@@ -28,7 +28,8 @@ _GLOBAL_IDS = {"embed": W_EMBED, "lm_head": W_LM_HEAD, "final_norm": W_FINAL_NOR
 
 EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weight", "eagle_reset", "eagle_prefill",
            "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_step", "eagle_vanilla_step", "eagle_generate",
-           "eagle_set_hint", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile",
+           "eagle_set_hint", "eagle_set_page_table", "eagle_set_buffer", "eagle_force_tree", "eagle_expand_level",
+           "eagle_force_accept", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile",
            "eagle_last_error", "eagle_version"]
 
 
@@ -88,6 +89,11 @@ def load_library(need_gpu_runtime: bool = True):
     lib.eagle_generate.argtypes = [vp, i32, pi32, i32, i32, pi32, pi32, ctypes.POINTER(ctypes.c_float)]
     lib.eagle_set_hint.argtypes = [vp, i32, pi32, i32, ctypes.c_float, ctypes.c_float, ctypes.c_uint64]
     lib.eagle_get_buffer.argtypes = [vp, i32, i32, vp, sz]
+    lib.eagle_set_page_table.argtypes = [vp, pi32]
+    lib.eagle_set_buffer.argtypes = [vp, i32, i32, vp, sz]
+    lib.eagle_force_tree.argtypes = [vp, i32, pi32]
+    lib.eagle_expand_level.argtypes = [vp, i32]
+    lib.eagle_force_accept.argtypes = [vp, pi32, pi32, pi32]
     lib.eagle_get_kv_row.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     lib.eagle_set_profiling.argtypes = [vp, i32]
     lib.eagle_get_profile.argtypes = [vp, ctypes.POINTER(EagleProfile), i32]
@@ -244,6 +250,41 @@ class Eagle:
         self._chk(self.lib.eagle_generate(self.h, 0, _p32(p), len(p), max_new, _p32(out), ctypes.byref(n), ctypes.byref(tau)))
         self.n_active = 1
         return out[:n.value].copy(), float(tau.value)
+
+    # -- injection
+    @property
+    def pages_per_slot(self) -> int:
+        return (self.cfg.max_seq + self.cfg.page_tokens - 1) // self.cfg.page_tokens
+
+    def set_page_table(self, table: Sequence[int]) -> None:
+        t = np.ascontiguousarray(table, dtype=np.int32)
+        if t.size != self.max_batch * self.pages_per_slot:
+            raise ValueError("page table must hold max_batch * pages_per_slot entries")
+        self._chk(self.lib.eagle_set_page_table(self.h, _p32(t)))
+
+    def set_buffer(self, which: int, arr: np.ndarray, seq: int = 0) -> None:
+        dt = np.int32 if which == BUF_TREE_TOKENS else np.float32
+        a = np.ascontiguousarray(arr, dtype=dt)
+        self._chk(self.lib.eagle_set_buffer(self.h, which, seq, a.ctypes.data, a.nbytes))
+
+    def force_tree(self, seq: int, tokens: Sequence[int]) -> None:
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        if t.size != self.M:
+            raise ValueError("one token per tree node")
+        self._chk(self.lib.eagle_force_tree(self.h, seq, _p32(t)))
+
+    def expand_level(self, level: int) -> None:
+        self._chk(self.lib.eagle_expand_level(self.h, level))
+
+    def force_accept(self, paths, lens, bonus) -> None:
+        """paths: one list of node indices per active slot (starting with 0)."""
+        D1 = self.D + 1
+        p = np.zeros((self.n_active, D1), np.int32)
+        for s, pth in enumerate(paths):
+            p[s, :len(pth)] = pth
+        ln = np.ascontiguousarray(lens, dtype=np.int32)
+        bo = np.ascontiguousarray(bonus, dtype=np.int32)
+        self._chk(self.lib.eagle_force_accept(self.h, _p32(p), _p32(ln), _p32(bo)))
 
     # -- buffers
     def get_buffer(self, which: int, seq: int = 0) -> np.ndarray:

@@ -14,6 +14,18 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define EAGLE_MAX_CHILD 8
 #define EAGLE_PREFILL_CHUNK 128
 
+// Per-work-group time stamps (100 MHz wall clock) exist only in a library built with -DEAGLE_TRACE (a profiling build);
+// in the product build the macros expand to nothing and no kernel carries a trace store.
+#ifdef EAGLE_TRACE
+#define TRACE_PTR(expr) (expr)
+#define TRACE_STAMP(tr, i) do { if (tr) (tr)[i] = wall_clock64(); } while (0)
+#define TRACE_STAMP_AFTER(tr, i, value_used) do { if (tr) (tr)[i] = wall_clock64() + ((value_used) == 123.456f ? 1 : 0); } while (0)
+#else
+#define TRACE_PTR(expr) nullptr
+#define TRACE_STAMP(tr, i) do { (void)(tr); } while (0)
+#define TRACE_STAMP_AFTER(tr, i, value_used) do { (void)(tr); } while (0)
+#endif
+
 // ---------------------------------------------------------------- bf16
 __host__ __device__ inline bf16_t f32_to_bf16(float f) {   // round to nearest even
   uint32_t u = __builtin_bit_cast(uint32_t, f);

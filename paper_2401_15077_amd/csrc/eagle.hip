@@ -86,11 +86,9 @@ struct eagle_ctx {
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
   float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
-  bool xk_on = true;                   // other bf16 GEMMs: streamed-activation split-K where the fetch model prefers it
-  bool half_on = true;                 // whole-K QKV: half-row-block work split where it balances better
-  bool fullk_on = true;                // wide GEMMs (QKV, gate/up, LM head) as whole-K work-groups without partials
-  unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0;   // time stamps of the trace_sel-th fast-path GEMM of a verify phase
-  int n_cu = 256;
+  unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0, expand_trace = 0;   // profiling builds only
+  int n_cu = 256;                      // compute units of the device (queried by eagle_init; 256 assumed when no device is visible)
+  int device = 0;
   // host mirror
   std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
   int n_active = 0;
@@ -199,7 +197,7 @@ static int check_cfg(const eagle_config* c) {
   if (!c) return fail(EAGLE_EINVAL, "null config");
   if (c->dtype != EAGLE_F32 && c->dtype != EAGLE_BF16) return fail(EAGLE_EINVAL, "dtype must be EAGLE_F32 or EAGLE_BF16");
   if (c->kv_dtype != EAGLE_F32 && c->kv_dtype != EAGLE_BF16) return fail(EAGLE_EINVAL, "kv_dtype must be EAGLE_F32 or EAGLE_BF16");
-  if (c->n_layers < 1 || c->d_model < 16 || c->d_model % 16) return fail(EAGLE_EINVAL, "d_model must be a positive multiple of 16");
+  if (c->n_layers < 1 || c->d_model < 64 || c->d_model % 64) return fail(EAGLE_EINVAL, "d_model must be a positive multiple of 64");
   if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 32) return fail(EAGLE_EINVAL, "head_dim must be 32, 64 or 128");
   if (c->n_heads < 1 || c->n_kv_heads < 1 || c->n_heads % c->n_kv_heads) return fail(EAGLE_EINVAL, "n_heads must be a multiple of n_kv_heads");
   if ((c->n_heads * c->head_dim) % 32 || (c->n_kv_heads * c->head_dim) % 32) return fail(EAGLE_EINVAL, "attention widths must be multiples of 32");
@@ -338,10 +336,24 @@ static size_t layout(eagle_ctx* c) {
   return (a.off + 255) & ~(size_t)255;
 }
 
+// Compute units of the current device.  The work splits are planned for at most 256 of them (the per-row-group
+// buffers are sized for that); without a visible device (size queries on a build machine) 256 is assumed.
+static int query_cus(int* device) {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    *device = -1;
+    return 256;
+  }
+  *device = dev;
+  return std::min(n, 256);
+}
+
 static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   c->cfg = *cfg;
+  c->n_cu = query_cus(&c->device);
   rc = build_tree(cfg, &c->tree_h);
   if (rc) return rc;
   c->f32 = cfg->dtype == EAGLE_F32;
@@ -421,11 +433,11 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   for (int i = 0; i < 4; ++i)
     if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "event creation failed"); }
   memset(&c->prof, 0, sizeof(c->prof));
+#ifdef EAGLE_TRACE
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
-  if (const char* t = getenv("EAGLE_FULLK")) c->fullk_on = atoi(t) != 0;
-  if (const char* t = getenv("EAGLE_XK")) c->xk_on = atoi(t) != 0;
-  if (const char* t = getenv("EAGLE_HALF")) c->half_on = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
+  if (getenv("EAGLE_EXPAND_TRACE")) c->expand_trace = 1;
+#endif
   *out = c;
   return EAGLE_OK;
 }
@@ -759,7 +771,6 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   g.W = w.w; g.wps = w.plane_stride; g.NRB = w.NRB; g.KS = w.KS; g.Npad = w.Npad; g.N = w.N;
   g.XF = XF; g.S = p.S; g.groups = p.groups; g.lanes = p.lanes; g.kparts = p.kparts;
   g.PT = c->PT2; g.counters = c->cnt_gemm;
-  { static int dbg = -1; if (dbg < 0) { const char* e = getenv("EAGLE_DEBUG_GEMM"); dbg = e ? atoi(e) : 0; } g.dbg = dbg; }
   g.trace = (c->gemm_no++ == c->trace_sel && p.groups * p.S <= 1024) ? c->trace : nullptr;
   if (g.ssq_out && p.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
   if (groups_out) *groups_out = p.groups;
@@ -771,11 +782,11 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   }
   hipError_t e;
   // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials)
-  const bool fullk = c->fullk_on && !c->f32 && !g.row_w && g.epi != EPI_RESID && w.NRB >= c->n_cu && g.dbg == 0;
+  const bool fullk = !c->f32 && !g.row_w && g.epi != EPI_RESID && w.NRB >= c->n_cu;
   // other matrices of the bf16 configuration: split-K, with the activations either staged in LDS (plan2) or streamed
   // (plan_xk), whichever the fetch model prices lower
   PlanXK px; px.S = 0;
-  if (!fullk && c->xk_on && !c->f32 && g.dbg == 0) {
+  if (!fullk && !c->f32) {
     px = plan_xk(w.NRB, w.KS, c->NXP, c->n_cu, (size_t)w.Npad * 32, c->pt2_floats);
     const int kt_s = (w.KS + p.S - 1) / p.S;
     const long staged = (long)R * kt_s + (long)c->NXP * kt_s + 2L * p.S * R * 4 + 40;
@@ -793,7 +804,7 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
     // QKV: split by half row blocks where that lowers the largest share (3 halves instead of 2 blocks at d = 4096);
     // a run of u halves touches at most u/2 + 1 blocks
     const int umax = (2 * w.NRB + grid - 1) / grid;
-    const bool half = c->half_on && g.epi == EPI_QKV && umax < 2 * nrmax && umax / 2 + 1 <= 2 &&
+    const bool half = g.epi == EPI_QKV && umax < 2 * nrmax && umax / 2 + 1 <= 2 &&
                       (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
     if (half) e = launch_fk<2, true>(g, grid, c->stream);
     else e = nrmax <= 2 ? launch_fk<2>(g, grid, c->stream) : nrmax == 3 ? launch_fk<3>(g, grid, c->stream) : launch_fk<4>(g, grid, c->stream);
@@ -1048,7 +1059,7 @@ static int do_draft(eagle_ctx* c) {
   dim3 g0(1, B);
   const float* src1 = fast1 ? c->h2 : nullptr;   // fast path: k_expand stores the root's head feature itself
   if (g.vocab > 32768) k_expand<true><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, src1, c->node_f, g.d_model, D1);
-  else k_expand<false><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, getenv("EAGLE_EXPAND_TRACE") ? c->trace : nullptr, src1, c->node_f, g.d_model, D1);
+  else k_expand<false><<<g0, 1024, 0, c->stream>>>(-1, B, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, c->expand_trace ? c->trace : nullptr, src1, c->node_f, g.d_model, D1);
   LAUNCH_CHECK();
   for (int lev = 1; lev < c->D; ++lev) {
     int nr = c->tree_h.n_level_rows[lev];
@@ -1086,13 +1097,24 @@ static int do_verify(eagle_ctx* c) {
   return EAGLE_OK;
 }
 
-static int do_accept(eagle_ctx* c) {
+static int do_compact(eagle_ctx* c);
+
+// Acceptance + commit.  pbuf / qbuf (fp32 [n_active][vocab] each, non-greedy only) and row_amax (int [n_active][M], greedy
+// only) are the kernels' scratch: the caller's workspace, or the library's static device array.
+static int do_accept(eagle_ctx* c, float* pbuf, float* qbuf, int* row_amax) {
   if (c->phase != 2) return fail(EAGLE_ESTATE, "eagle_accept needs verified logits (call eagle_verify first)");
   const eagle_config& g = c->cfg;
   const int B = c->n_active;
-  if (g.temperature <= 0.f) { k_row_argmax<<<B * c->M, 1024, 0, c->stream>>>(c->L, g.vocab, c->row_amax); LAUNCH_CHECK(); }
-  k_accept<<<B, 1024, 0, c->stream>>>(c->tree_d, c->st, c->L, c->draft_logits, c->tree_tok, g.vocab, g.temperature, g.seed, c->pbuf, c->qbuf, c->path, c->tok_out, c->len_out, c->row_amax);
+  if (g.temperature <= 0.f) { k_row_argmax<<<B * c->M, 1024, 0, c->stream>>>(c->L, g.vocab, row_amax); LAUNCH_CHECK(); }
+  k_accept<<<B, 1024, 0, c->stream>>>(c->tree_d, c->st, c->L, c->draft_logits, c->tree_tok, g.vocab, g.temperature, g.seed, pbuf, qbuf, c->path, c->tok_out, c->len_out, row_amax);
   LAUNCH_CHECK();
+  return do_compact(c);
+}
+static int do_accept(eagle_ctx* c) { return do_accept(c, c->pbuf, c->qbuf, c->row_amax); }
+
+static int do_compact(eagle_ctx* c) {
+  const eagle_config& g = c->cfg;
+  const int B = c->n_active;
   dim3 grid(4, g.n_layers + 1, B);
   KVCache kv = kv_for(c, 0);
   if (c->kv_f32) k_compact<float><<<grid, 256, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->kc, c->vc, c->layer_stride, g.n_layers, kv, c->F, c->pend_f, g.d_model);
@@ -1232,6 +1254,91 @@ extern "C" int eagle_generate(eagle_ctx* c, int32_t seq, const int32_t* prompt, 
   *n_out = produced;
   if (mean_accept_len) *mean_accept_len = steps ? (float)emitted / steps : 0.f;
   return EAGLE_OK;
+}
+
+// ---------------------------------------------------------------------------- injection (lock-step tests, external schedulers)
+extern "C" int eagle_set_page_table(eagle_ctx* c, const int32_t* table) {
+  if (!c || !table) return fail(EAGLE_EINVAL, "null argument");
+  if (c->n_active != 0) return fail(EAGLE_ESTATE, "the page table can only change while no sequence is active (after eagle_init / eagle_reset)");
+  const size_t n = (size_t)c->cfg.max_batch * c->pps;
+  std::vector<char> seen(n, 0);
+  for (size_t i = 0; i < n; ++i) {
+    if (table[i] < 0 || (size_t)table[i] >= n || seen[table[i]]) return fail(EAGLE_EINVAL, "page table entry %zu = %d: entries must be a permutation of 0..%zu", i, table[i], n - 1);
+    seen[table[i]] = 1;
+  }
+  HIPCHK(hipMemcpyAsync(c->page_table, table, n * 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_set_buffer(eagle_ctx* c, int32_t which, int32_t seq, const void* src, size_t bytes) {
+  if (!c || !src) return fail(EAGLE_EINVAL, "null argument");
+  const eagle_config& g = c->cfg;
+  if (seq < 0 || seq >= g.max_batch) return fail(EAGLE_EINVAL, "slot %d out of range", seq);
+  void* dst = nullptr;
+  size_t need = 0;
+  switch (which) {
+    case EAGLE_BUF_LOGITS: dst = c->L + (size_t)seq * c->M * g.vocab; need = (size_t)c->M * g.vocab * 4; break;
+    case EAGLE_BUF_FEATURES: dst = c->F + (size_t)seq * c->M * g.d_model; need = (size_t)c->M * g.d_model * 4; break;
+    case EAGLE_BUF_DRAFT_LOGITS: dst = c->draft_logits + (size_t)seq * c->M * g.vocab; need = (size_t)c->M * g.vocab * 4; break;
+    case EAGLE_BUF_DRAFT_FEATURES: dst = c->node_f + (size_t)seq * c->M * g.d_model; need = (size_t)c->M * g.d_model * 4; break;
+    case EAGLE_BUF_TREE_TOKENS: {
+      const int32_t* t = (const int32_t*)src;
+      if (bytes == (size_t)c->M * 4)
+        for (int v = 0; v < c->M; ++v) if (t[v] < 0 || t[v] >= g.vocab) return fail(EAGLE_EINVAL, "token %d of node %d outside the vocabulary", t[v], v);
+      dst = c->tree_tok + (size_t)seq * c->M; need = (size_t)c->M * 4; break;
+    }
+    default: return fail(EAGLE_EINVAL, "buffer %d cannot be written", which);
+  }
+  if (bytes != need) return fail(EAGLE_EINVAL, "source of %zu bytes, the buffer holds %zu", bytes, need);
+  HIPCHK(hipMemcpyAsync(dst, src, need, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_force_tree(eagle_ctx* c, int32_t seq, const int32_t* tokens) {
+  if (!c || !tokens) return fail(EAGLE_EINVAL, "null argument");
+  if (c->phase != 1) return fail(EAGLE_ESTATE, "eagle_force_tree replaces the tokens of a drafted tree (call eagle_draft_tree first)");
+  if (seq < 0 || seq >= c->n_active) return fail(EAGLE_EINVAL, "slot %d is not active", seq);
+  return eagle_set_buffer(c, EAGLE_BUF_TREE_TOKENS, seq, tokens, (size_t)c->M * 4);
+}
+
+extern "C" int eagle_expand_level(eagle_ctx* c, int32_t level) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  if (c->n_active < 1) return fail(EAGLE_ESTATE, "no active sequence");
+  if (level != -1 && (level < 1 || level >= c->D)) return fail(EAGLE_EINVAL, "level must be -1 (the root) or 1..depth-1");
+  const eagle_config& g = c->cfg;
+  const int nr = level < 0 ? 1 : c->tree_h.n_level_rows[level];
+  if (nr == 0) return EAGLE_OK;
+  dim3 grid(nr, c->n_active);
+  if (g.vocab > 32768) k_expand<true><<<grid, 1024, 0, c->stream>>>(level, c->n_active, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, nullptr, c->node_f, g.d_model, nr);
+  else k_expand<false><<<grid, 1024, 0, c->stream>>>(level, c->n_active, c->tree_d, c->st, c->draft_logits, c->tree_tok, c->on_path, c->hint, g.vocab, g.temperature, g.seed, nullptr, nullptr, c->node_f, g.d_model, nr);
+  LAUNCH_CHECK();
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_force_accept(eagle_ctx* c, const int32_t* path, const int32_t* len, const int32_t* bonus) {
+  if (!c || !path || !len || !bonus) return fail(EAGLE_EINVAL, "null argument");
+  if (c->phase != 2) return fail(EAGLE_ESTATE, "eagle_force_accept needs a verified tree (call eagle_verify first)");
+  const int B = c->n_active, D1 = c->D + 1;
+  for (int s = 0; s < B; ++s) {
+    if (len[s] < 1 || len[s] > D1) return fail(EAGLE_EINVAL, "slot %d: length %d outside 1..%d", s, len[s], D1);
+    if (path[s * D1] != 0) return fail(EAGLE_EINVAL, "slot %d: a path starts at the root (node 0)", s);
+    for (int i = 1; i < len[s]; ++i) {
+      const int v = path[s * D1 + i];
+      if (v < 1 || v >= c->M || c->tree_h.parent[v] != path[s * D1 + i - 1]) return fail(EAGLE_EINVAL, "slot %d: node %d at step %d is not a child of its predecessor", s, v, i);
+    }
+    if (bonus[s] < 0 || bonus[s] >= c->cfg.vocab) return fail(EAGLE_EINVAL, "slot %d: bonus token outside the vocabulary", s);
+  }
+  HIPCHK(hipMemcpyAsync(c->path, path, (size_t)B * D1 * 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->len_out, len, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(hipMemcpyAsync(c->row_amax, bonus, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));   // (idle scratch: B ints)
+  HIPCHK(hipStreamSynchronize(c->stream));
+  k_force_commit<<<(B + 63) / 64, 64, 0, c->stream>>>(c->tree_d, c->st, c->path, c->len_out, c->row_amax, c->tree_tok, c->tok_out, B);
+  LAUNCH_CHECK();
+  int rc = do_compact(c);
+  if (rc) return rc;
+  return fetch_results(c, nullptr, nullptr, nullptr);
 }
 
 // ---------------------------------------------------------------------------- test / bench access

@@ -572,8 +572,8 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
   __shared__ float shv[16];
   __shared__ int shi[16];
   const int seq = blockIdx.y;
-  unsigned long long* tr = (trace && threadIdx.x == 0 && blockIdx.x == 0 && seq == 0) ? trace : nullptr;
-  if (tr) tr[0] = wall_clock64();
+  unsigned long long* tr = TRACE_PTR((trace && threadIdx.x == 0 && blockIdx.x == 0 && seq == 0) ? trace : nullptr);
+  TRACE_STAMP(tr, 0);
   const int v = level < 0 ? 0 : tree->level_rows[level][blockIdx.x];
   const int M = tree->M;
   // The node's own head feature (the row of the pass that produced these logits) goes to node_f here when the caller
@@ -627,7 +627,7 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
   int picked[EAGLE_MAX_CHILD];                                 // thread 0 writes the results once, after the rounds
 #pragma unroll
   for (int q = 0; q < EAGLE_MAX_CHILD; ++q) picked[q] = 0;
-  if (tr) tr[1] = wall_clock64() + (x[0] == 12345.f ? 1 : 0);
+  TRACE_STAMP_AFTER(tr, 1, x[0]);
   if constexpr (!BIGV) {
     // Scores stay in registers.  Every thread offers its best entry; the block picks the overall best (ties to the
     // lower token id); only the thread that owned it removes it and looks for its next best.
@@ -645,7 +645,7 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
     float lv = -INFINITY; int li = 0x7fffffff;
 #pragma unroll
     for (int u = 0; u < XPT; ++u) better(lv, li, x[u], u * 1024 + (int)threadIdx.x);
-    if (tr) tr[2] = wall_clock64() + (lv == 12345.f ? 1 : 0);
+    TRACE_STAMP_AFTER(tr, 2, lv);
     for (int r = 0; r < nk; ++r) {
       float bv = lv; int bi = li;
       block_argmax(bv, bi, shv, shi);
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(1024) void k_expand(int level /*-1 = root*/, int n_
         on_path[seq * M + childs[q]] = (hinted >= 0 && picked[q] == hinted);
       }
   }
-  if (tr) tr[3] = wall_clock64();
+  TRACE_STAMP(tr, 3);
 }
 
 // softmax(x / T) over V entries into p (block-wide), returns nothing; sh >= 16 floats
@@ -729,31 +729,34 @@ __device__ inline void block_softmax(const float* x, float* p, int V, float invT
   __syncthreads();
 }
 
-// smallest x with cumsum(p)[x] > u * sum(p); block-wide, result broadcast through *res (shared)
-__device__ inline int block_inverse_cdf(const float* p, int V, float u, float* sh_f /*>= blockDim.x*/, int* res) {
+// smallest x with cumsum(p)[x] > u * sum(p); block-wide, result broadcast through *res (shared).  The running sum is
+// carried in fp64: with 32000 entries a bin is ~3e-5 wide, which an fp32 running sum cannot resolve -- the draw would
+// depend on the order of the additions instead of on p.  (Thread chunks, then a prefix over the chunk sums, then a
+// sequential walk of the one chunk that holds the target: fixed order.)
+__device__ inline int block_inverse_cdf(const float* p, int V, float u, double* sh_d /*>= blockDim.x + 1*/, int* res) {
   const int nt = blockDim.x;
   const int per = (V + nt - 1) / nt;
   const int j0 = threadIdx.x * per, j1 = min(V, j0 + per);
-  float s = 0.f;
-  for (int j = j0; j < j1; ++j) s += p[j];
-  sh_f[threadIdx.x] = s;
+  double s = 0.0;
+  for (int j = j0; j < j1; ++j) s += (double)p[j];
+  sh_d[threadIdx.x] = s;
   __syncthreads();
   if (threadIdx.x == 0) {
-    float tot = 0.f;
-    for (int i = 0; i < nt; ++i) { float t = sh_f[i]; sh_f[i] = tot; tot += t; }   // exclusive prefix, fixed order
-    sh_f[nt] = tot;
+    double tot = 0.0;
+    for (int i = 0; i < nt; ++i) { double t = sh_d[i]; sh_d[i] = tot; tot += t; }   // exclusive prefix, fixed order
+    sh_d[nt] = tot;
     *res = V - 1;
   }
   __syncthreads();
-  const float target = u * sh_f[nt];
-  float c = sh_f[threadIdx.x];
-  float nxt = threadIdx.x + 1 < nt ? sh_f[threadIdx.x + 1] : sh_f[nt];
+  const double target = (double)u * sh_d[nt];
+  double c = sh_d[threadIdx.x];
+  const double nxt = threadIdx.x + 1 < nt ? sh_d[threadIdx.x + 1] : sh_d[nt];
   __syncthreads();
   if (j0 < j1 && c <= target && (target < nxt || threadIdx.x + 1 == nt || j1 == V)) {
     int found = -1, last_pos = -1;
     for (int j = j0; j < j1; ++j) {
       if (p[j] > 0.f) last_pos = j;
-      c += p[j];
+      c += (double)p[j];
       if (c > target) { found = j; break; }
     }
     if (found < 0) found = last_pos;            // rounding left the running sum just short of the target
@@ -770,7 +773,7 @@ __global__ __launch_bounds__(1024) void k_choose(SeqState st, int seq0, const fl
                                                  int prefill_n, int max_pend) {
   __shared__ float shv[16];
   __shared__ int shi[16];
-  __shared__ float sh_f[1025];
+  __shared__ double sh_f[1025];
   __shared__ int res;
   const int seq = seq0 + blockIdx.x;
   const float* lg = logits + (size_t)seq * V;
@@ -825,7 +828,7 @@ __global__ __launch_bounds__(1024) void k_accept(const TreeDev* tree, SeqState s
                                                  const int* __restrict__ amax /*[seq][M], greedy only*/) {
   __shared__ float shv[16];
   __shared__ int shi[16];
-  __shared__ float sh_f[1025];
+  __shared__ double sh_f[1025];
   __shared__ int res, s_next;
   const int seq = blockIdx.x, M = tree->M, D1 = tree->D + 1;
   int cur = 0, len = 1, bonus = 0;
@@ -939,6 +942,25 @@ __global__ __launch_bounds__(256) void k_compact(const TreeDev* tree, SeqState s
       *(u32x4*)(cache + kv_offset(kv, seq, base + i, kvh) + off) = val;
     }
   }
+}
+
+// Commit of paths handed in by the caller instead of found by k_accept (lock-step tests drive the engine along the
+// oracle's choices with it): the bookkeeping at the end of k_accept, for every sequence.  bonus[seq] = the token that
+// follows the accepted drafts.  k_compact runs afterwards as in a normal step.
+__global__ void k_force_commit(const TreeDev* tree, SeqState st, const int* path /*[seq][D+1]*/, const int* len_p,
+                               const int* bonus, const int* tree_tok, int* tok_out, int n_seq) {
+  const int seq = blockIdx.x * blockDim.x + threadIdx.x;
+  if (seq >= n_seq) return;
+  const int M = tree->M, D1 = tree->D + 1, len = len_p[seq], n = st.n_tok[seq];
+  for (int i = 1; i < len; ++i) {
+    const int t = tree_tok[seq * M + path[seq * D1 + i]];
+    tok_out[seq * D1 + i - 1] = t;
+    st.tokens[(size_t)seq * st.tok_stride + n + i - 1] = t;
+  }
+  tok_out[seq * D1 + len - 1] = bonus[seq];
+  st.tokens[(size_t)seq * st.tok_stride + n + len - 1] = bonus[seq];
+  st.commit_base[seq] = st.ctx_len[seq];
+  st.n_tok[seq] = n + len; st.ctx_len[seq] += len; st.n_pend[seq] = len; st.step_no[seq] += 1;
 }
 
 // ============================================================================ MoE router

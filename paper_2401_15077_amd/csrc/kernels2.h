@@ -128,8 +128,7 @@ struct Gemm2 {
   float* logits; int out_kind, V, only_last_row;
   const float* row_w;                     // MoE: per-row routing weight applied to this GEMM's result (nullptr = 1)
   const int* skip_flag;                   // MoE: the whole launch is a no-op when *skip_flag == 0 (no row uses the expert)
-  unsigned long long* trace;              // optional [work-group][8] time stamps (100 MHz wall clock) of this launch
-  int dbg;                                // timing experiments only (0 in normal use): 1 = no epilogue, 2 = stop after the main loop, 4 = no main loop
+  unsigned long long* trace;              // profiling builds (-DEAGLE_TRACE) only: [work-group][8] time stamps of this launch
 };
 
 // out[0..3] = sum over the K splits of rows nA..nA+3, out[4..7] the same for rows nB..nB+3 (nA, nB multiples of 4,
@@ -454,8 +453,8 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   const int ks0 = (unsigned)s * uKS / uS, ks1 = (unsigned)(s + 1) * uKS / uS, kt = ks1 - ks0;
   const int la = (unsigned)w % ulanes, kb_i = (unsigned)w / ulanes;
   const int kb = (unsigned)kb_i * (unsigned)kt / ukparts, ke = (unsigned)(kb_i + 1) * (unsigned)kt / ukparts;
-  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
-  if (tr) tr[0] = wall_clock64();
+  unsigned long long* tr = TRACE_PTR((g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr);
+  TRACE_STAMP(tr, 0);
   int nr = 0;
   for (int j = 0; j < RW; ++j) nr += (rb0 + la + j * g.lanes < rb1) ? 1 : 0;
   nr = __builtin_amdgcn_readfirstlane(nr);
@@ -469,7 +468,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   }
   // the first weight tiles are requested before anything else (a wave with fewer row blocks keeps more k-steps in flight)
   u32x4 pre[DEPTH * RW * NWP];
-  if (!(g.dbg & 4)) k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
+  k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
 
   // row facts and the 1/rms inputs the epilogue will want: requested now, used (by the last work-group) much later
   RowPre rp;
@@ -514,10 +513,9 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   __syncthreads();
-  if (tr) tr[1] = wall_clock64();
-  if (!(g.dbg & 4)) k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane, pre);
-  if (tr) tr[2] = wall_clock64();
-  if (g.dbg & 2) { if (acc[0][0] == 123.456f) g.PT[0] = 1.f; return; }
+  TRACE_STAMP(tr, 1);
+  k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane, pre);
+  TRACE_STAMP(tr, 2);
   // waves that split K inside the work-group: sum through LDS in k-part order
   if (g.kparts > 1) {
     __syncthreads();                                          // the X slice is no longer needed
@@ -562,8 +560,8 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     if (s_last) __hip_atomic_store(g.counters + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
-  if (tr) tr[3] = wall_clock64();
-  if (!s_last || (g.dbg & 1)) return;
+  TRACE_STAMP(tr, 3);
+  if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   const int n0 = rb0 * 32, n1 = min(rb1 * 32, g.N);
   if (n1 <= n0) return;
@@ -575,7 +573,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
     default: epilogue_logits(g, n0, n1, rstd_s, rp); break;
   }
-  if (tr) tr[4] = wall_clock64();
+  TRACE_STAMP(tr, 4);
 }
 
 // ---- full-K variant for wide matrices (QKV, gate/up, LM head) ----------------------------------------------------------
@@ -689,8 +687,8 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
   float* red = (float*)smem;                                    // [8][NRMAX][16][64]
   if (g.skip_flag && *g.skip_flag == 0) return;                 // MoE: no row selected this expert (uniform over the grid)
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
-  if (tr) tr[0] = wall_clock64();
+  unsigned long long* tr = TRACE_PTR((g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr);
+  TRACE_STAMP(tr, 0);
   const unsigned G = gridDim.x;
   int rb0, rb1, row_lo = 0, row_hi = 32;                        // rows [row_lo, 32) of the first block, [0, row_hi) of the last
   if constexpr (HALF) {
@@ -738,7 +736,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
     }
   }
   fk_stream_dispatch<NWP, NXP, NRMAX, HALF>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane, &hw);
-  if (tr) tr[2] = wall_clock64() + (acc[0][0] == 123.456f ? 1 : 0);
+  TRACE_STAMP_AFTER(tr, 2, acc[0][0]);
   // park every wave's sums in LDS
 #pragma unroll
   for (int j = 0; j < NRMAX; ++j)
@@ -807,7 +805,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
       }
     }
   }
-  if (tr) tr[4] = wall_clock64();
+  TRACE_STAMP(tr, 4);
 }
 
 // ---- split-K with streamed activations (narrow matrices with a long K: O, down) ------------------------------------------
@@ -826,8 +824,8 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
   float* red = (float*)smem;                                    // [8][NRMAX][16][64]
   if (g.skip_flag && *g.skip_flag == 0) return;                 // uniform over the whole grid
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  unsigned long long* tr = (g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr;
-  if (tr) tr[0] = wall_clock64();
+  unsigned long long* tr = TRACE_PTR((g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr);
+  TRACE_STAMP(tr, 0);
   const unsigned uS = g.S, ugroups = g.groups, uNRB = g.NRB, uKS = g.KS;
   const int s = blockIdx.x % uS, grp = blockIdx.x / uS;
   const int rb0 = (unsigned)grp * uNRB / ugroups, rb1 = (unsigned)(grp + 1) * uNRB / ugroups;
@@ -857,7 +855,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
     }
   }
   fk_stream_dispatch<NWP, NXP, NRMAX>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane);
-  if (tr) tr[2] = wall_clock64() + (acc[0][0] == 123.456f ? 1 : 0);
+  TRACE_STAMP_AFTER(tr, 2, acc[0][0]);
 #pragma unroll
   for (int j = 0; j < NRMAX; ++j)
     if (j < nr)
@@ -878,7 +876,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
     f32x4 o; o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3];
     coh_store16(g.PT, pt_quad_bytes(s, g.Npad, (rb0 + j) * 32 + 8 * i + 4 * (lane >> 5), lane & 31), o);
   }
-  if (tr) tr[3] = wall_clock64();
+  TRACE_STAMP(tr, 3);
   publish_wait();
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -898,7 +896,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
     case EPI_SWIGLU: epilogue_swiglu<NXP>(g, n0, n1, rstd_s); break;
     default: epilogue_logits(g, n0, n1, rstd_s, rp); break;
   }
-  if (tr) tr[4] = wall_clock64();
+  TRACE_STAMP(tr, 4);
 }
 
 // Rows of a pass that need no GEMM in front: h = embedding of the row's token.  Writes h, XF(h * gain) and the
@@ -1032,8 +1030,8 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
   // blockIdx.z = (sequence of the pass, 32-row block of that sequence's rows); MT = 32-row tiles of the XF output
   const int split = blockIdx.x, hd = blockIdx.y, seq_l = blockIdx.z / rblocks, rblk = blockIdx.z % rblocks;
   // optional time stamps: 0 entered, 1 keys/values consumed, 2 waves merged + partials written, 3 arrived, 4 splits merged
-  unsigned long long* tr = (trace && threadIdx.x == 0 && seq_l == 0) ? trace + ((size_t)hd * gridDim.x + split) * 8 : nullptr;
-  if (tr) tr[0] = wall_clock64();
+  unsigned long long* tr = TRACE_PTR((trace && threadIdx.x == 0 && seq_l == 0) ? trace + ((size_t)hd * gridDim.x + split) * 8 : nullptr);
+  TRACE_STAMP(tr, 0);
   const int r0 = seq_l * pass.rows_per_seq + 32 * rblk;
   const int R = min(32, pass.rows_per_seq - 32 * rblk);
   const int kvh = hd / (H / kv.n_kv_heads);
@@ -1174,7 +1172,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
       }
     }
   }
-  if (tr) tr[1] = wall_clock64();
+  TRACE_STAMP(tr, 1);
   __syncthreads();                          // every wave is done with the query fragments that o_s overlays
   // merge the 4 waves through LDS: o_s[w][d][q], d = 32b + 8(r/4) + 4hh + r%4
 #pragma unroll
@@ -1219,7 +1217,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
       coh_store16(part_o, po + 16, v1);
     }
   }
-  if (tr) tr[2] = wall_clock64();
+  TRACE_STAMP(tr, 2);
   if (n_splits == 1) return;
   if (q2 < R && tid < 32) {
     const size_t ofs = (((size_t)(r0 + q2) * H + hd) * n_splits + split) * 2;
@@ -1235,7 +1233,7 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     if (s_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
-  if (tr) tr[3] = wall_clock64();
+  TRACE_STAMP(tr, 3);
   if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   // merge the splits of (sequence, head): thread = (row, CW-wide column chunk), one item per thread in the usual
@@ -1266,5 +1264,5 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
 #pragma unroll
     for (int h8 = 0; h8 < CW / 8; ++h8) xf_store8(xf_out, r0 + r, hd * DH + d0 + 8 * h8, MT, KSX, nplanes, x + 8 * h8);
   }
-  if (tr) tr[4] = wall_clock64();
+  TRACE_STAMP(tr, 4);
 }

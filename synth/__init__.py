@@ -156,6 +156,10 @@ SHAPES: Dict[str, ModelShape] = {
     "mini-gqa": ModelShape("mini-gqa", "bf16", 2, 256, 8, 2, 32, 384, 512),
     "mini-moe": ModelShape("mini-moe", "bf16", 2, 256, 8, 2, 32, 320, 512, n_experts=4, experts_per_tok=2,
                            draft_moe=True),
+    # the tiny model with the LLaMA vocabulary (child selection / acceptance over 32000 entries at small cost) and with
+    # a vocabulary beyond 32768 entries
+    "tiny-v32k": ModelShape("tiny-v32k", "fp32", 2, 256, 4, 4, 64, 688, 32000),
+    "tiny-v40k": ModelShape("tiny-v40k", "fp32", 2, 256, 4, 4, 64, 688, 40000),
 }
 
 # ----------------------------------------------------------------------------- draft trees
@@ -224,16 +228,20 @@ def _layer_specs(s: ModelShape, moe: bool) -> List[Tuple[str, Tuple[int, ...], f
     return out
 
 
-def tensor_specs(s: ModelShape) -> List[Tuple[str, int, Tuple[int, ...], float, float]]:
+def tensor_specs(s: ModelShape, head_recipe: str = "scaled") -> List[Tuple[str, int, Tuple[int, ...], float, float]]:
     """All tensors of target + EAGLE head: (name, tid, shape, std, mean).
     Matrices are row-major [out_features, in_features], N(0, 0.02) except the head's FC; norm gains ~ N(1, 0.02);
-    FC bias ~ N(0, 0.02)."""
+    FC bias ~ N(0, 0.02).  head_recipe "scaled" (default) keeps the head's features at the target's scale;
+    "literal" draws every head matrix from N(0, 0.02) like the target's."""
+    if head_recipe not in ("scaled", "literal"):
+        raise ValueError(head_recipe)
+    literal = head_recipe == "literal"
     specs = [("embed", 1, (s.vocab, s.d_model), 0.02, 0.0),
              ("lm_head", 2, (s.vocab, s.d_model), 0.02, 0.0),
              ("final_norm", 3, (s.d_model,), 0.02, 1.0),
              # std (2d)^-1/2: the FC output keeps the scale of its input, as a trained head's features keep the scale of
              # the target's; with 0.02 the head's feature norm grows 1.8-2.6x per tree level (fan-in 2d)
-             ("head.fc_w", 4, (s.d_model, 2 * s.d_model), (2 * s.d_model) ** -0.5, 0.0),
+             ("head.fc_w", 4, (s.d_model, 2 * s.d_model), 0.02 if literal else (2 * s.d_model) ** -0.5, 0.0),
              ("head.fc_b", 5, (s.d_model,), 0.02, 0.0)]
     for li in range(s.n_layers):
         for k, (nm, shp, std, mean) in enumerate(_layer_specs(s, s.n_experts > 0)):
@@ -241,7 +249,7 @@ def tensor_specs(s: ModelShape) -> List[Tuple[str, int, Tuple[int, ...], float, 
     for nm, shp, std, mean in _layer_specs(s, s.n_experts > 0 and s.draft_moe):
         # the head has no final norm, so its residual branches are scaled down (output projections with gain 1/4):
         # f-hat then has the scale of the target's normalised feature, which is what a trained head regresses to
-        if nm in ("wo", "down"):
+        if nm in ("wo", "down") and not literal:
             std = 0.25 * shp[-1] ** -0.5
         specs.append((f"head.layer.{nm}", 512 + _LAYER_FIELDS.index(nm), shp, std, mean))
     return specs
@@ -261,13 +269,13 @@ def gen_tensor(s: ModelShape, seed: int, spec, fmt: str) -> np.ndarray:
     return normal(seed, tid, n, std, mean, fmt).reshape(shp)
 
 
-def iter_weights(s: ModelShape, seed: int, fmt: str) -> Iterator[Tuple[str, np.ndarray]]:
-    for spec in tensor_specs(s):
+def iter_weights(s: ModelShape, seed: int, fmt: str, head_recipe: str = "scaled") -> Iterator[Tuple[str, np.ndarray]]:
+    for spec in tensor_specs(s, head_recipe):
         yield spec[0], gen_tensor(s, seed, spec, fmt)
 
 
-def make_weights(s: ModelShape, seed: int, fmt: str) -> Dict[str, np.ndarray]:
-    return dict(iter_weights(s, seed, fmt))
+def make_weights(s: ModelShape, seed: int, fmt: str, head_recipe: str = "scaled") -> Dict[str, np.ndarray]:
+    return dict(iter_weights(s, seed, fmt, head_recipe))
 
 
 def oracle_fmt(s: ModelShape) -> str:

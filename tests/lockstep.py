@@ -34,8 +34,11 @@ def check_prefill(eng, orc, prompt, tol, margin_thr=2e-2, seq=0):
     err = float(np.abs(lg - orc.prefill_logits[-1]).max())
     assert err <= tol, f"prefill logits differ by {err}"
     if first_g != first_o:
-        lo = orc.prefill_logits[-1]
-        gap = float(lo[first_o] - lo[first_g])
+        if orc.T == 0.0:
+            lo = orc.prefill_logits[-1]
+            gap = float(lo[first_o] - lo[first_g])
+        else:                                   # a draw: how close the drawn point lay to the edge of its bin
+            gap = orc.first_margin
         assert gap < margin_thr, f"first token differs ({first_g} vs {first_o}) with margin {gap}"
         orc.x[-1] = int(first_g)
     return err

@@ -207,10 +207,12 @@ def test_moe_stochastic_lockstep():
     """The Mixtral-shaped configuration's mode in small: MoE target and head, temperature 1, seeded draws."""
     s, eng, orc = make_pair("mini-moe", "T15", seed=8, temperature=1.0, rng_seed=77, n_layers=2, dtype=np.float64)
     prompt = synth.prompt(8, 24, s.vocab)
-    check_prefill(eng, orc, prompt, TOL["bf16"], margin_thr=1e-3)
+    # draws: a differing draw is excused only if the oracle's point lay within 5 % of a bin width of the bin's edge
+    # (bf16 weights: the two sides' probabilities differ by ~1e-3 relative)
+    check_prefill(eng, orc, prompt, TOL["bf16"], margin_thr=5e-2)
     st = Stats()
     for _ in range(10):
-        lockstep_step(eng, orc, st, TOL["bf16"], margin_thr=1e-3, stoch_margin=1e-3)
+        lockstep_step(eng, orc, st, TOL["bf16"], margin_thr=1e-3, stoch_margin=5e-2)
     print(f"moe stochastic: steps={st.steps} tau={st.tau:.2f} max|dL|={st.max_logit_err:.2e} excused={st.excused_tree_slots}/{st.excused_accepts}", flush=True)
     assert list(eng.get_buffer(pkg.BUF_TOKENS)) == orc.x and st.excused_accepts <= 1
     eng.close()
