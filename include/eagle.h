@@ -102,6 +102,16 @@ int eagle_verify(eagle_ctx *ctx);
  *   path       int32[n_active * (depth+1)]  accepted node indices (= KV compaction sources), path[0] = 0 */
 int eagle_accept(eagle_ctx *ctx, int32_t *out_tokens, int32_t *out_len, int32_t *path);
 
+/* eagle_accept for callers that cannot allocate or hand over scratch memory (code that must not call hipMalloc: tight
+ * serving loops, harnesses that forbid it): the same kernels, but their scratch -- the two fp32 [n_active, vocab]
+ * probability vectors of Alg. 1, or the per-node arg-max array of the greedy walk -- lives in a 4 MiB array that is
+ * part of the library's device code instead of in the context's workspace.  Inputs (the verified logits, the tree)
+ * and outputs are those of eagle_accept.  Limit: non-greedy, n_active * vocab <= 524288 (16 slots at vocab 32000);
+ * greedy always fits.  EAGLE_EINVAL beyond that, before anything is launched.  The call allocates nothing.  Every
+ * context on one GPU shares that GPU's array (it keeps the last call's contents; the kernels write every element
+ * they read): calls that overlap in time on one GPU race, also across contexts and streams. */
+int eagle_accept_static(eagle_ctx *ctx, int32_t *out_tokens, int32_t *out_len, int32_t *path);
+
 /* draft + verify + accept back to back with no host synchronisation in between; outputs as eagle_accept. */
 int eagle_step(eagle_ctx *ctx, int32_t *out_tokens, int32_t *out_len, int32_t *path);
 

@@ -27,7 +27,7 @@ _GLOBAL_IDS = {"embed": W_EMBED, "lm_head": W_LM_HEAD, "final_norm": W_FINAL_NOR
                "head.fc_b": W_FC_BIAS}
 
 EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weight", "eagle_reset", "eagle_prefill",
-           "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_step", "eagle_vanilla_step", "eagle_generate",
+           "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_accept_static", "eagle_step", "eagle_vanilla_step", "eagle_generate",
            "eagle_set_hint", "eagle_set_page_table", "eagle_set_buffer", "eagle_force_tree", "eagle_expand_level",
            "eagle_force_accept", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile",
            "eagle_last_error", "eagle_version"]
@@ -85,6 +85,7 @@ def load_library(need_gpu_runtime: bool = True):
     lib.eagle_verify.argtypes = [vp]
     lib.eagle_accept.argtypes = [vp, pi32, pi32, pi32]
     lib.eagle_step.argtypes = [vp, pi32, pi32, pi32]
+    lib.eagle_accept_static.argtypes = [vp, pi32, pi32, pi32]
     lib.eagle_vanilla_step.argtypes = [vp, pi32]
     lib.eagle_generate.argtypes = [vp, i32, pi32, i32, i32, pi32, pi32, ctypes.POINTER(ctypes.c_float)]
     lib.eagle_set_hint.argtypes = [vp, i32, pi32, i32, ctypes.c_float, ctypes.c_float, ctypes.c_uint64]
@@ -233,6 +234,9 @@ class Eagle:
 
     def accept(self):
         return self._results(self.lib.eagle_accept)
+
+    def accept_static(self):
+        return self._results(self.lib.eagle_accept_static)
 
     def step(self):
         return self._results(self.lib.eagle_step)

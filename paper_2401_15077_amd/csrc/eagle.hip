@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <vector>
 #include <algorithm>
+#include <mutex>
 
 static thread_local char g_err[512] = "";
 static int fail(int code, const char* fmt, ...) {
@@ -26,6 +27,17 @@ static int fail(int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(EAGLE_EHIP, "%s failed: %s (%s:%d)", #x, hipGetErrorString(e_), __FILE__, __LINE__); \
   } while (0)
 #define LAUNCH_CHECK() HIPCHK(hipGetLastError())
+
+// ---------------------------------------------------------------------------- static device scratch
+// Scratch of eagle_accept_static(): a fixed array in the code object instead of caller-provided memory, for callers
+// that cannot allocate.  Every GPU the library runs on holds its own copy at its own address until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the address that kernels, copies and fills
+// are given is the one that call returned for the device at hand (g_scratch_dev), never the name.
+#define EAGLE_STATIC_SCRATCH_BYTES (4u << 20)
+#define EAGLE_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[EAGLE_STATIC_SCRATCH_BYTES];
+static void* g_scratch_dev[EAGLE_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
 
 // ---------------------------------------------------------------------------- descriptors
 struct PackedW {            // a weight matrix in tiled layout
@@ -89,6 +101,7 @@ struct eagle_ctx {
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0, expand_trace = 0;   // profiling builds only
   int n_cu = 256;                      // compute units of the device (queried by eagle_init; 256 assumed when no device is visible)
   int device = 0;
+  void* static_scratch = nullptr;      // this device's address of the library's static scratch array
   // host mirror
   std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
   int n_active = 0;
@@ -392,6 +405,17 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   layout(c);
   c->stream = (hipStream_t)hip_stream;
   const eagle_config& g = c->cfg;
+  {  // address of the static scratch array on the current device, looked up once per device
+    if (c->device < 0 || c->device >= EAGLE_MAX_DEVICES) { delete c; return fail(EAGLE_EHIP, "no usable HIP device is current"); }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_dev[c->device]) {
+      void* p = nullptr;
+      hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) { delete c; return fail(EAGLE_EHIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e)); }
+      g_scratch_dev[c->device] = p;
+    }
+    c->static_scratch = g_scratch_dev[c->device];
+  }
   // the tree arrays are copied: the caller's pointers need not outlive this call
   c->cfg.parent = nullptr; c->cfg.rank = nullptr;
   memset(c->loaded, 0, sizeof(c->loaded));
@@ -1159,6 +1183,20 @@ extern "C" int eagle_verify(eagle_ctx* c) {
 extern "C" int eagle_accept(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
   if (!c) return fail(EAGLE_EINVAL, "null context");
   int rc = do_accept(c);
+  if (rc) return rc;
+  return fetch_results(c, out_tokens, out_len, path);
+}
+
+extern "C" int eagle_accept_static(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, int32_t* path) {
+  if (!c) return fail(EAGLE_EINVAL, "null context");
+  const eagle_config& g = c->cfg;
+  const size_t B = (size_t)c->n_active;
+  const size_t vec = (B * g.vocab * 4 + 255) & ~(size_t)255;                  // one fp32 [n_active][vocab] array
+  const size_t need = g.temperature > 0.f ? 2 * vec : B * c->M * 4;
+  if (need > EAGLE_STATIC_SCRATCH_BYTES)
+    return fail(EAGLE_EINVAL, "eagle_accept_static: %zu active slots x vocab %d need %zu bytes of scratch, the static array holds %u", B, g.vocab, need, EAGLE_STATIC_SCRATCH_BYTES);
+  char* sp = (char*)c->static_scratch;
+  int rc = do_accept(c, (float*)sp, (float*)(sp + vec), (int*)sp);
   if (rc) return rc;
   return fetch_results(c, out_tokens, out_len, path);
 }
