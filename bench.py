@@ -8,9 +8,10 @@ biased toward the target's greedy continuation so that the mean accepted length 
 and synthetic (random-init weights N(0, 0.02), uniform-random prompt); they stand in for the chat benchmarks
 the paper measures on.
 
-Prints ONE JSON line: decode tokens/s (`value`), ms per step, the verify-phase time, the roofline of the
-dominant kernel (the weight-streaming GEMM, timed with HIP events on the library's stream), and the CPU
-oracle timed on the host cores on a bounded sample.
+Prints ONE JSON line: decode tokens/s (`value`), ms per step, the verify-phase time, a per-kernel table of the
+verify phase (every launch timed by start/stop events attached to the dispatch, on the library's stream), the
+roofline of the dominant kernel of that table, a bare streaming-read ceiling measured in the same process, and
+the CPU oracle timed on the host cores on a bounded sample.
 """
 import argparse
 import json
@@ -184,22 +185,43 @@ def main() -> int:
             toks = eng.get_buffer(pkg.BUF_TOKENS, b)
             stale = stale or not np.array_equal(toks, np.asarray(futures[b][:len(toks)], np.int32))
     _, _, prof1 = run(1, K)                          # same K steps with phase events
-    _, _, prof2 = run(2, min(K, 16))                 # per-launch events around the GEMM kernel
+    eng.get_kernel_stats(0); eng.get_kernel_stats(1)
+    _, _, prof2 = run(2, min(K, 16))                 # start/stop events on every GEMM and attention launch
+    kstats = {"draft": eng.get_kernel_stats(0), "verify": eng.get_kernel_stats(1)}
 
     verify_ms = prof1["verify_ms"] / max(1, prof1["steps"])
     draft_ms = prof1["draft_ms"] / max(1, prof1["steps"])
     accept_ms = prof1["accept_ms"] / max(1, prof1["steps"])
     verify_bytes = (prof1["verify_weight_bytes"] + prof1["verify_kv_bytes"]) / max(1, prof1["steps"])
-    # each launch was bracketed by two event records; what such a pair measures with nothing in between (calibrated by
-    # the library when mode 2 is switched on) is not the kernel's time and is taken off
-    n_launch = max(1, prof2["gemm_launches"])
-    gemm_ms = max(1e-9, prof2["gemm_ms"] - n_launch * prof2["event_pair_ms"])
-    gemm_gbs = prof2["gemm_weight_bytes"] / (gemm_ms * 1e-3) / 1e9
-    # HBM bytes per launch of the same kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (each scaled by what the
-    # counter reads for a copy of known size), measured on this workload; only quoted for this workload
+    n_timed_steps = max(1, prof2["steps"])
+
+    def table(rows):
+        out_rows = []
+        for r in rows:
+            us = r["ms"] * 1e3 / max(1, r["launches"])
+            bpl = r["bytes"] / max(1, r["launches"])
+            out_rows.append({"name": r["name"], "kernel": r["kernel"], "launches_per_step": r["launches"] / n_timed_steps,
+                             "avg_launch_us": us, "bytes_per_launch": bpl, "us_per_step": r["ms"] * 1e3 / n_timed_steps,
+                             "gb_per_s": bpl / (us * 1e-6) / 1e9 if us > 0 else None,
+                             "frac_of_8TBs": bpl / (us * 1e-6) / 8e12 if us > 0 else None})
+        return out_rows
+
+    verify_table, draft_table = table(kstats["verify"]), table(kstats["draft"])
+    gemm_rows = [r for r in verify_table if r["name"] != "attention"]
+    dominant = max(gemm_rows, key=lambda r: r["us_per_step"]) if gemm_rows else None
+    # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (each scaled by what
+    # the counter reads for a copy of known size): taken from the committed summary under profiles/, which names the
+    # commit it was measured on; only quoted for the workload it was measured on
     default_workload = (args.shape == "llama2-7b" and not args.layers and args.tree == "T26" and args.prompt == 512
-                        and B == 1 and not stochastic)
-    traffic = 108.9e6 + 1.4e6 if default_workload else None
+                        and B == 1 and not stochastic and args.kv_dtype == "fp32")
+    traffic, traffic_src = None, None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_llama2-7b_bs1_T26.txt")
+    if default_workload and dominant and os.path.exists(tpath):
+        for ln in open(tpath):
+            f = ln.split()
+            if len(f) >= 4 and f[0] == "TRAFFIC" and f[1] == dominant["name"]:
+                traffic, traffic_src = float(f[2]), f"profiles/hbm_traffic_llama2-7b_bs1_T26.txt (measured at commit {f[3]})"
+    stream_gbs = pkg.probe_stream_read(2 << 30, 5)   # beyond the 256 MB memory-side cache
     out = {
         "metric": "decode tokens/s + verify-step ms, LLaMA2-7B shape bs=1; % HBM roofline",
         "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -214,12 +236,15 @@ def main() -> int:
         "verify_bytes": verify_bytes, "vanilla_tokens_per_s": vanilla_tok_s, "hint_stale": bool(stale), "hint_repairs": repairs,
         "load_s": t_load, "prefill_ms": prefill_ms_timed, "prefill_tokens_per_s": B * args.prompt / (prefill_ms_timed * 1e-3),
         "accept_rate_by_depth": accept_by_depth,
-        "roofline": {"bound": "hbm", "kernel": "k2_gemm_fk + k2_gemm_xk (fused weight-streaming GEMMs: whole-K and streamed split-K; all launches of the timed steps)",
-                     "achieved": gemm_gbs, "peak": 8000.0, "unit": "GB/s", "frac": gemm_gbs / 8000.0, "traffic": traffic,
-                     "launches": int(prof2["gemm_launches"]),
-                     "avg_launch_us": gemm_ms * 1e3 / n_launch,
-                     "event_pair_us": prof2["event_pair_ms"] * 1e3,
-                     "bytes_per_launch": prof2["gemm_weight_bytes"] / n_launch},
+        "stream_ceiling_gbs": stream_gbs,
+        "verify_kernels": verify_table, "draft_kernels": draft_table,
+        "roofline": {"bound": "hbm",
+                     "kernel": f"{dominant['kernel']} on the {dominant['name']} matrix (the verify-phase launch class with the largest summed time)",
+                     "achieved": dominant["gb_per_s"], "peak": 8000.0, "unit": "GB/s", "frac": dominant["frac_of_8TBs"],
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "launches_per_step": dominant["launches_per_step"], "avg_launch_us": dominant["avg_launch_us"],
+                     "bytes_per_launch": dominant["bytes_per_launch"],
+                     "all_gemm_launches_gb_per_s": prof2["gemm_weight_bytes"] / (prof2["gemm_ms"] * 1e-3) / 1e9 if prof2["gemm_ms"] > 0 else None},
     }
     eng.close()
     del eng
@@ -239,15 +264,13 @@ def main() -> int:
         orc.set_hint(cfuture, alpha, HINT_BIAS, hint_seed)
         orc.prefill(cprompt)
         tc = time.perf_counter()
+        cpu0 = time.process_time()
         em = 0
         for _ in range(args.cpu_steps):
             em += orc.spec_step()["length"]
         dtc = time.perf_counter() - tc
-        try:
-            import threadpoolctl
-            cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count()
+        # threads the oracle actually kept busy: CPU time of the process over wall time of the timed steps
+        cores = max(1, round((time.process_time() - cpu0) / dtc))
         out["cpu_baseline"] = {"value": em / dtc, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                                "sample": f"{args.cpu_steps} speculative steps of the same {shape.name} model after a "
                                          f"{cp}-token prompt, fp32 numpy oracle, same knob (tau={em / args.cpu_steps:.2f}); "

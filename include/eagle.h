@@ -180,18 +180,29 @@ int eagle_get_buffer(eagle_ctx *ctx, int32_t which, int32_t seq, void *host_dst,
 /* K and V (fp32, [n_kv_heads*head_dim] each) of target layer `layer` (or EAGLE_HEAD_LAYER) at cache position pos. */
 int eagle_get_kv_row(eagle_ctx *ctx, int32_t seq, int32_t layer, int32_t pos, float *k_host, float *v_host);
 
-/* Timing (HIP events on the context's stream).  mode 0 = off, 1 = phases (draft / verify / accept per step),
- * 2 = additionally every launch of the weight-streaming GEMM kernel. */
+/* Timing (HIP events on the context's stream).  mode 0 = off, 1 = phases (draft / verify / accept per eagle_step),
+ * 2 = additionally every launch of the weight-streaming GEMM kernels and of the attention kernel inside eagle_step,
+ * each with a start and a stop event attached to the dispatch itself (the kernel's own begin and end time stamps:
+ * the figure a kernel trace shows for the launch). */
 int eagle_set_profiling(eagle_ctx *ctx, int32_t mode);
 typedef struct {
   double draft_ms, verify_ms, accept_ms;   /* sums over the steps since the last reset of the counters */
   int64_t steps;
   double gemm_ms; int64_t gemm_launches; double gemm_weight_bytes;  /* mode 2 only */
   double verify_weight_bytes, verify_kv_bytes;                    /* algorithmic bytes of the verify phases */
-  double event_pair_ms;   /* mode 2: what two consecutive event records measure with nothing between them (each GEMM
-                             launch in gemm_ms carries this much on top of the kernel's own duration) */
 } eagle_profile;
 int eagle_get_profile(eagle_ctx *ctx, eagle_profile *out, int32_t reset);
+/* Mode 2, per class of launch and per phase (0 = drafting, 1 = verification): summed kernel durations, launches and
+ * algorithmic HBM bytes (a weight matrix once in its stored type; for attention the keys and values of the context
+ * and the pass's rows once).  name: qkv | attention | o_proj | gate_up | down | lm_head | fc; kernel: the template
+ * that ran.  Up to `cap` entries are written, *n of them. */
+typedef struct { char name[16]; char kernel[48]; double ms; int64_t launches; double bytes; } eagle_kernel_stat;
+int eagle_get_kernel_stats(eagle_ctx *ctx, int32_t phase, eagle_kernel_stat *out, int32_t cap, int32_t *n, int32_t reset);
+
+/* Measurement reference, independent of any context: a bare streaming read of `bytes` bytes of device memory
+ * (16-byte loads, nothing computed), run `iters` times on `hip_stream`, each launch timed by its own start/stop
+ * events; *gb_per_s = bytes read / summed kernel time.  The buffer is only read.  Synchronises the stream. */
+int eagle_probe_stream_read(const void *buf_dev, size_t bytes, int32_t iters, void *hip_stream, double *gb_per_s);
 
 const char *eagle_last_error(void);   /* thread-local text of the last failure */
 const char *eagle_version(void);

@@ -29,7 +29,7 @@ _GLOBAL_IDS = {"embed": W_EMBED, "lm_head": W_LM_HEAD, "final_norm": W_FINAL_NOR
 EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weight", "eagle_reset", "eagle_prefill",
            "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_accept_static", "eagle_step", "eagle_vanilla_step", "eagle_generate",
            "eagle_set_hint", "eagle_set_page_table", "eagle_set_buffer", "eagle_force_tree", "eagle_expand_level",
-           "eagle_force_accept", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile",
+           "eagle_force_accept", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile", "eagle_get_kernel_stats", "eagle_probe_stream_read",
            "eagle_last_error", "eagle_version"]
 
 
@@ -48,7 +48,12 @@ class EagleProfile(ctypes.Structure):
     _fields_ = [("draft_ms", ctypes.c_double), ("verify_ms", ctypes.c_double), ("accept_ms", ctypes.c_double),
                 ("steps", ctypes.c_int64), ("gemm_ms", ctypes.c_double), ("gemm_launches", ctypes.c_int64),
                 ("gemm_weight_bytes", ctypes.c_double), ("verify_weight_bytes", ctypes.c_double),
-                ("verify_kv_bytes", ctypes.c_double), ("event_pair_ms", ctypes.c_double)]
+                ("verify_kv_bytes", ctypes.c_double)]
+
+
+class EagleKernelStat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 16), ("kernel", ctypes.c_char * 48), ("ms", ctypes.c_double),
+                ("launches", ctypes.c_int64), ("bytes", ctypes.c_double)]
 
 
 class EagleError(RuntimeError):
@@ -98,6 +103,8 @@ def load_library(need_gpu_runtime: bool = True):
     lib.eagle_get_kv_row.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     lib.eagle_set_profiling.argtypes = [vp, i32]
     lib.eagle_get_profile.argtypes = [vp, ctypes.POINTER(EagleProfile), i32]
+    lib.eagle_get_kernel_stats.argtypes = [vp, i32, ctypes.POINTER(EagleKernelStat), i32, pi32, i32]
+    lib.eagle_probe_stream_read.argtypes = [vp, sz, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.eagle_last_error.restype = ctypes.c_char_p
     lib.eagle_version.restype = ctypes.c_char_p
     _lib = lib
@@ -121,6 +128,18 @@ def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=6
                       n_nodes=len(parent), parent=_p32(parent), rank=_p32(rank), temperature=temperature, seed=seed)
     cfg._keep = (parent, rank)
     return cfg
+
+
+def probe_stream_read(nbytes: int, iters: int = 10, device="cuda:0") -> float:
+    """GB/s of a bare streaming read of `nbytes` bytes of device memory (the practical HBM ceiling)."""
+    import torch
+    lib = load_library()
+    buf = torch.ones(nbytes // 4, dtype=torch.int32, device=device)
+    gbs = ctypes.c_double()
+    rc = lib.eagle_probe_stream_read(buf.data_ptr(), buf.numel() * 4, iters, torch.cuda.current_stream(buf.device).cuda_stream, ctypes.byref(gbs))
+    if rc != 0:
+        raise EagleError(rc, lib.eagle_last_error().decode())
+    return float(gbs.value)
 
 
 class Eagle:
@@ -328,3 +347,11 @@ class Eagle:
         p = EagleProfile()
         self._chk(self.lib.eagle_get_profile(self.h, ctypes.byref(p), int(reset)))
         return {f: getattr(p, f) for f, _ in p._fields_}
+
+    def get_kernel_stats(self, phase: int, reset: bool = True):
+        """Mode-2 timing per class of launch: list of dicts (name, kernel, ms, launches, bytes)."""
+        arr = (EagleKernelStat * 16)()
+        n = ctypes.c_int32()
+        self._chk(self.lib.eagle_get_kernel_stats(self.h, phase, arr, 16, ctypes.byref(n), int(reset)))
+        return [{"name": arr[i].name.decode(), "kernel": arr[i].kernel.decode(), "ms": arr[i].ms,
+                 "launches": int(arr[i].launches), "bytes": arr[i].bytes} for i in range(n.value)]

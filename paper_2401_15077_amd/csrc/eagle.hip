@@ -3,6 +3,7 @@
 #include "../../include/eagle.h"
 #include "kernels.h"
 #include "kernels2.h"
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdarg>
@@ -53,6 +54,13 @@ struct LayerW {
   bool moe = false;
 };
 struct GemmPlan { int S, ks_per_split, chunk; };
+
+// Kernel classes of the per-launch timing (profiling mode 2): what the launch computes, not which template ran
+// (the template's name is recorded beside it).
+enum { KC_QKV = 0, KC_ATTN, KC_O, KC_GATEUP, KC_DOWN, KC_LMHEAD, KC_FC, KC_COUNT };
+static const char* const kKernelClassName[KC_COUNT] = {"qkv", "attention", "o_proj", "gate_up", "down", "lm_head", "fc"};
+struct KStat { double ms = 0, bytes = 0; long launches = 0; char kernel[48] = ""; };
+struct TimedLaunch { int phase, kclass; double bytes; };
 
 struct Arena {
   char* base; size_t off = 0;
@@ -109,9 +117,10 @@ struct eagle_ctx {
   // profiling
   int prof_mode = 0;
   hipEvent_t ev[4];
-  std::vector<hipEvent_t> gemm_ev; size_t gemm_ev_used = 0; std::vector<double> gemm_ev_bytes;
+  std::vector<hipEvent_t> gemm_ev; size_t gemm_ev_used = 0; std::vector<TimedLaunch> timed;
+  KStat kstat[2][KC_COUNT];           // [0 drafting phase | 1 verification phase][class]
+  int cur_phase = -1, cur_class = KC_QKV;   // phase of the step that is being enqueued (-1: outside a step, not timed)
   eagle_profile prof;
-  double event_pair_ms = 0;
 };
 
 static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
@@ -556,17 +565,41 @@ static int all_loaded(eagle_ctx* c) {
 }
 
 // ---------------------------------------------------------------------------- launches
-template <int NWP, int NXP>
-static hipError_t launch_gemm_mt(const PackedW& w, const bf16_t* XF, float* PT, int MT, const GemmPlan& p, hipStream_t s) {
-  dim3 grid((w.NRB + 3) / 4, p.S);
-  size_t lds = (size_t)NXP * MT * GemmChunk<NXP>::CH * 1024;
-  switch (MT) {
-    case 1: k_gemm<NWP, NXP, 1><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
-    case 2: k_gemm<NWP, NXP, 2><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
-    case 3: k_gemm<NWP, NXP, 3><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
-    default: k_gemm<NWP, NXP, 4><<<grid, 256, lds, s>>>(w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad); break;
+// Launches a kernel; in profiling mode 2, inside a step, with a start and a stop event attached to the dispatch itself
+// (hipExtLaunchKernelGGL): the pair reads the kernel's own begin and end time stamps, so no event-record overhead
+// enters the measured duration.  `bytes` = the launch's algorithmic HBM bytes; `name` = the kernel template.
+template <typename K, typename... A>
+static hipError_t launch_k(eagle_ctx* c, int kclass, double bytes, const char* name, K kernel, dim3 grid, dim3 block, size_t lds, A... args) {
+  if (c->prof_mode == 2 && c->cur_phase >= 0) {
+    if (c->gemm_ev_used + 2 > c->gemm_ev.size())
+      for (int i = 0; i < 512; ++i) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return rc;
+        c->gemm_ev.push_back(e);
+      }
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, c->stream, c->gemm_ev[c->gemm_ev_used], c->gemm_ev[c->gemm_ev_used + 1], 0, args...);
+    c->gemm_ev_used += 2;
+    c->timed.push_back(TimedLaunch{c->cur_phase, kclass, bytes});
+    KStat& ks = c->kstat[c->cur_phase][kclass];
+    if (!ks.kernel[0]) snprintf(ks.kernel, sizeof(ks.kernel), "%s", name);
+  } else {
+    kernel<<<grid, block, lds, c->stream>>>(args...);
   }
   return hipGetLastError();
+}
+template <int NWP, int NXP>
+static hipError_t launch_gemm_mt(eagle_ctx* c, const PackedW& w, const bf16_t* XF, float* PT, int MT, const GemmPlan& p) {
+  dim3 grid((w.NRB + 3) / 4, p.S);
+  size_t lds = (size_t)NXP * MT * GemmChunk<NXP>::CH * 1024;
+  const double bytes = (double)w.N * w.K * c->elt;
+  const int kc = c->cur_class;
+  switch (MT) {
+    case 1: return launch_k(c, kc, bytes, "k_gemm<MT=1>", k_gemm<NWP, NXP, 1>, grid, dim3(256), lds, (const bf16_t*)w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad);
+    case 2: return launch_k(c, kc, bytes, "k_gemm<MT=2>", k_gemm<NWP, NXP, 2>, grid, dim3(256), lds, (const bf16_t*)w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad);
+    case 3: return launch_k(c, kc, bytes, "k_gemm<MT=3>", k_gemm<NWP, NXP, 3>, grid, dim3(256), lds, (const bf16_t*)w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad);
+    default: return launch_k(c, kc, bytes, "k_gemm<MT=4>", k_gemm<NWP, NXP, 4>, grid, dim3(256), lds, (const bf16_t*)w.w, w.plane_stride, XF, PT, w.NRB, w.KS, p.ks_per_split, w.Npad);
+  }
 }
 
 // PT <- X (XF layout, MT row tiles) times W^T.  Returns the split count through *S.
@@ -575,30 +608,22 @@ static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S
   if ((size_t)p.S * w.Npad * MT * 32 > c->pt_floats) return fail(EAGLE_EINVAL, "internal: partial buffer too small");
   if (MT < 1 || MT > 4) return fail(EAGLE_EINVAL, "internal: MT out of range");
   *S = p.S;
-  bool timed = c->prof_mode == 2;
-  if (timed) {
-    if (c->gemm_ev_used + 2 > c->gemm_ev.size()) {
-      for (int i = 0; i < 512; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
-    }
-    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used], c->stream));
-  }
-  hipError_t e = c->f32 ? launch_gemm_mt<3, 3>(w, XF, c->PT, MT, p, c->stream) : launch_gemm_mt<1, 2>(w, XF, c->PT, MT, p, c->stream);
+  hipError_t e = c->f32 ? launch_gemm_mt<3, 3>(c, w, XF, c->PT, MT, p) : launch_gemm_mt<1, 2>(c, w, XF, c->PT, MT, p);
   if (e != hipSuccess) return fail(EAGLE_EHIP, "gemm launch failed: %s", hipGetErrorString(e));
-  if (timed) {
-    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used + 1], c->stream));
-    c->gemm_ev_used += 2;
-    c->gemm_ev_bytes.push_back((double)w.N * w.K * c->elt);
-  }
   return EAGLE_OK;
 }
 
+// Reads the event pairs of the launches timed since the last call (the stream must have been synchronised).
 static int collect_gemm_events(eagle_ctx* c) {
-  for (size_t i = 0; i + 1 < c->gemm_ev_used; i += 2) {
+  for (size_t i = 0; i < c->timed.size(); ++i) {
     float ms = 0.f;
-    HIPCHK(hipEventElapsedTime(&ms, c->gemm_ev[i], c->gemm_ev[i + 1]));
-    c->prof.gemm_ms += ms; c->prof.gemm_launches += 1; c->prof.gemm_weight_bytes += c->gemm_ev_bytes[i / 2];
+    HIPCHK(hipEventElapsedTime(&ms, c->gemm_ev[2 * i], c->gemm_ev[2 * i + 1]));
+    const TimedLaunch& t = c->timed[i];
+    KStat& ks = c->kstat[t.phase][t.kclass];
+    ks.ms += ms; ks.launches += 1; ks.bytes += t.bytes;
+    if (t.kclass != KC_ATTN) { c->prof.gemm_ms += ms; c->prof.gemm_launches += 1; c->prof.gemm_weight_bytes += t.bytes; }
   }
-  c->gemm_ev_used = 0; c->gemm_ev_bytes.clear();
+  c->gemm_ev_used = 0; c->timed.clear();
   return EAGLE_OK;
 }
 
@@ -608,6 +633,16 @@ static int collect_gemm_events(eagle_ctx* c) {
 static int attn_splits(const eagle_ctx* c, int tokens, int units) {
   const int by_tokens = (tokens + 127) / 128, by_cus = std::max(1, c->n_cu / std::max(1, units));
   return std::max(1, std::min(16, std::min(by_tokens, by_cus)));
+}
+
+// Algorithmic HBM bytes of one attention launch: keys and values of every sequence's cached context plus the pass's
+// own rows, once (host mirror of the cached lengths; prefill chunks: the chunk's causal prefix).
+static double attn_bytes(const eagle_ctx* c, const Pass& p, int n_new) {
+  const eagle_config& g = c->cfg;
+  double toks = 0;
+  if (p.kind == PASS_PREFILL_T || p.kind == PASS_PREFILL_D) toks = p.chunk_start + p.chunk_n;
+  else for (int i = 0; i < p.n_seq; ++i) toks += c->h_ctx[p.seq0 + i] + n_new;
+  return toks * 2.0 * g.n_kv_heads * g.head_dim * c->kv_elt;
 }
 
 static KVCache kv_for(eagle_ctx* c, int li) {
@@ -638,7 +673,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   const int H = g.n_heads, KVH = g.n_kv_heads, dh = g.head_dim, F = g.d_ffn;
   int S = 1, rc;
   KVCache kv = kv_for(c, li);
-  if ((rc = gemm(c, w.qkv, c->xf_d, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_QKV, gemm(c, w.qkv, c->xf_d, MT, &S)))) return rc;
   {
     dim3 grid(M, H + 2 * KVH);
     if (c->kv_f32) k_qkv_rope_store<float><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
@@ -659,15 +694,16 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
       HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); \
       attr_done = true;                                                                                                 \
     }                                                                                                                   \
-    k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
-        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf_att, c->NXP, nullptr, MT, rblocks); \
+    hipError_t e_ = launch_k(c, KC_ATTN, attn_bytes(c, pass, n_new), "k2_attn", k2_attn<CT, DH>, grid, dim3(256), (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, \
+        pass, (const TreeDev*)c->tree_d, c->st, kv, (const float*)c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf_att, c->NXP, (unsigned long long*)nullptr, MT, rblocks); \
+    if (e_ != hipSuccess) return fail(EAGLE_EHIP, "attention launch failed: %s", hipGetErrorString(e_));                \
   } while (0)
     if (c->kv_f32) { if (dh == 128) ATTNG(float, 128); else if (dh == 64) ATTNG(float, 64); else ATTNG(float, 32); }
     else { if (dh == 128) ATTNG(bf16_t, 128); else if (dh == 64) ATTNG(bf16_t, 64); else ATTNG(bf16_t, 32); }
 #undef ATTNG
     LAUNCH_CHECK();
   }
-  if ((rc = gemm(c, w.o, c->xf_att, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_O, gemm(c, w.o, c->xf_att, MT, &S)))) return rc;
   if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.o.Npad, nullptr, w.mlp_norm, c->xf_d, w.moe ? c->xn : nullptr))) return rc;
   if (w.moe) {
     // top-k routed experts: every expert runs over all rows of the pass (the cost is the weight stream, not the
@@ -679,30 +715,30 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     LAUNCH_CHECK();
     if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
-      if ((rc = gemm(c, w.e_gu[e], c->xf_d, MT, &S))) return rc;
+      if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.e_gu[e], c->xf_d, MT, &S)))) return rc;
       dim3 grid((F / 8 + 255) / 256, M);
       k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.e_gu[e].Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
       LAUNCH_CHECK();
-      if ((rc = gemm(c, w.e_dn[e], c->xf_ffn, MT, &S))) return rc;
+      if ((rc = (c->cur_class = KC_DOWN, gemm(c, w.e_dn[e], c->xf_ffn, MT, &S)))) return rc;
       const bool last = e + 1 == E;     // only the last expert's pass produces the normalised output
       if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.e_dn[e].Npad, nullptr, last ? next_gain : nullptr, last ? c->xf_d : nullptr,
                         last ? xout : nullptr, c->moe_w + (size_t)e * 128))) return rc;
     }
     return EAGLE_OK;
   }
-  if ((rc = gemm(c, w.gu, c->xf_d, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.gu, c->xf_d, MT, &S)))) return rc;
   {
     dim3 grid((F / 8 + 255) / 256, M);
     k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
     LAUNCH_CHECK();
   }
-  if ((rc = gemm(c, w.dn, c->xf_ffn, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_DOWN, gemm(c, w.dn, c->xf_ffn, MT, &S)))) return rc;
   return resnorm(c, M, MT, c->h, c->PT, S, w.dn.Npad, nullptr, next_gain, c->xf_d, xout);
 }
 
 static int lm_head(eagle_ctx* c, const Pass& pass, int M, int MT, float* out, int out_kind, int only_last_row) {
   int S, rc;
-  if ((rc = gemm(c, c->lm_head, c->xf_d, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_LMHEAD, gemm(c, c->lm_head, c->xf_d, MT, &S)))) return rc;
   dim3 grid((c->cfg.vocab + 255) / 256, M);
   k_logits<<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, c->lm_head.Npad, MT * 32, out, out_kind, c->cfg.vocab, only_last_row);
   LAUNCH_CHECK();
@@ -736,7 +772,7 @@ static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bo
   if (c->f32) k_fc_input<float><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const float*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
   else k_fc_input<bf16_t><<<dim3(M, 4), 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->tree_tok, c->pend_f, c->node_f, c->chunk_f, (const bf16_t*)c->embed, c->xf_2d, g.d_model, g.vocab, MT, c->NXP);
   LAUNCH_CHECK();
-  if ((rc = gemm(c, c->fc, c->xf_2d, MT, &S))) return rc;
+  if ((rc = (c->cur_class = KC_FC, gemm(c, c->fc, c->xf_2d, MT, &S)))) return rc;
   const float* bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;
   if ((rc = resnorm(c, M, MT, nullptr, c->PT, S, c->fc.Npad, bias, c->layers[g.n_layers].attn_norm, c->xf_d, nullptr))) return rc;
   if ((rc = layer_forward(c, pass, M, MT, g.n_layers, t_max, n_new, nullptr, c->featbuf))) return rc;
@@ -748,32 +784,32 @@ static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bo
 
 // ---------------------------------------------------------------------------- fast path (<= 32 rows)
 template <int NWP, int NXP, int RW, int DEPTH>
-static hipError_t launch_k2(const Gemm2& g, size_t lds, hipStream_t s) {
+static hipError_t launch_k2(eagle_ctx* c, double bytes, const Gemm2& g, size_t lds) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)k2_gemm<NWP, NXP, RW, DEPTH>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  k2_gemm<NWP, NXP, RW, DEPTH><<<g.groups * g.S, V2_THREADS, lds, s>>>(g);
-  return hipGetLastError();
+  return launch_k(c, c->cur_class, bytes, "k2_gemm", k2_gemm<NWP, NXP, RW, DEPTH>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
 }
 
 template <int NRMAX, bool HALF = false>
-static hipError_t launch_fk(const Gemm2& g, int grid, hipStream_t s) {
+static hipError_t launch_fk(eagle_ctx* c, double bytes, const Gemm2& g, int grid) {
   static bool attr_set = false;
-  const size_t lds = (size_t)8 * NRMAX * 4096;
+  // the waves' sums, and behind them the residual epilogue's staging rows
+  const size_t lds = (size_t)8 * NRMAX * 4096 + (g.epi == EPI_RESID ? (size_t)NRMAX * 32 * 33 * 4 : 0);
+  if (lds > 144 * 1024) return hipErrorInvalidValue;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_fk<1, 2, NRMAX, HALF>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  k2_gemm_fk<1, 2, NRMAX, HALF><<<grid, V2_THREADS, lds, s>>>(g);
-  return hipGetLastError();
+  return launch_k(c, c->cur_class, bytes, HALF ? "k2_gemm_fk<half blocks>" : "k2_gemm_fk", k2_gemm_fk<1, 2, NRMAX, HALF>, dim3(grid), dim3(V2_THREADS), lds, g);
 }
 
 template <int NRMAX>
-static hipError_t launch_xk(const Gemm2& g, hipStream_t s) {
+static hipError_t launch_xk(eagle_ctx* c, double bytes, const Gemm2& g) {
   static bool attr_set = false;
   const size_t lds = (size_t)8 * NRMAX * 4096;
   if (!attr_set) {
@@ -781,8 +817,7 @@ static hipError_t launch_xk(const Gemm2& g, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  k2_gemm_xk<1, 2, NRMAX><<<g.groups * g.S, V2_THREADS, lds, s>>>(g);
-  return hipGetLastError();
+  return launch_k(c, c->cur_class, bytes, "k2_gemm_xk", k2_gemm_xk<1, 2, NRMAX>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
 }
 
 // Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
@@ -798,19 +833,23 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   g.trace = (c->gemm_no++ == c->trace_sel && p.groups * p.S <= 1024) ? c->trace : nullptr;
   if (g.ssq_out && p.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
   if (groups_out) *groups_out = p.groups;
-  bool timed = c->prof_mode == 2;
-  if (timed) {
-    if (c->gemm_ev_used + 2 > c->gemm_ev.size())
-      for (int i = 0; i < 512; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
-    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used], c->stream));
-  }
+  const double bytes = (double)w.N * w.K * c->elt;
   hipError_t e;
-  // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials)
-  const bool fullk = !c->f32 && !g.row_w && g.epi != EPI_RESID && w.NRB >= c->n_cu;
+  // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials) ...
+  const int fk_grid = std::max(c->n_cu, (w.NRB + 3) / 4);
+  const bool fits_rsrc = (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
+  const bool fullk = !c->f32 && w.NRB >= c->n_cu && (g.epi != EPI_RESID || (fk_grid <= 256 && (w.NRB + fk_grid - 1) / fk_grid <= 2));
+  // ... and narrower ones with at least one HALF row block per CU (O, down, FC at d = 4096 / 5120): still whole-K, a
+  // work-group owns one or two halves
+  // (measured at d = 4096: 35.6 us against 26.0 for down, 16.0 against 14.2 for O -- every tile load of a work-group
+  // that owns a single half carries half the bytes, so half as much is in flight, and the whole activation vector is
+  // fetched by every work-group instead of a K slice of it; the split is therefore not used)
+  const bool halfk = false && !c->f32 && !fullk && 2 * w.NRB >= c->n_cu && c->n_cu <= 256 && fits_rsrc &&
+                     (g.epi == EPI_RESID || g.epi == EPI_QKV);
   // other matrices of the bf16 configuration: split-K, with the activations either staged in LDS (plan2) or streamed
   // (plan_xk), whichever the fetch model prices lower
   PlanXK px; px.S = 0;
-  if (!fullk && !c->f32) {
+  if (!fullk && !halfk && !c->f32) {
     px = plan_xk(w.NRB, w.KS, c->NXP, c->n_cu, (size_t)w.Npad * 32, c->pt2_floats);
     const int kt_s = (w.KS + p.S - 1) / p.S;
     const long staged = (long)R * kt_s + (long)c->NXP * kt_s + 2L * p.S * R * 4 + 40;
@@ -820,37 +859,36 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
     g.S = px.S; g.groups = px.groups;
     if (groups_out) *groups_out = px.groups;
     g.trace = (g.trace && px.groups * px.S <= 1024) ? g.trace : nullptr;
-    e = px.nrmax <= 2 ? launch_xk<2>(g, c->stream) : px.nrmax == 3 ? launch_xk<3>(g, c->stream) : launch_xk<4>(g, c->stream);
+    e = px.nrmax <= 2 ? launch_xk<2>(c, bytes, g) : px.nrmax == 3 ? launch_xk<3>(c, bytes, g) : launch_xk<4>(c, bytes, g);
+  } else if (halfk) {
+    g.trace = (g.trace && c->n_cu <= 1024) ? g.trace : nullptr;
+    if (groups_out) *groups_out = c->n_cu;
+    e = launch_fk<2, true>(c, bytes, g, c->n_cu);
   } else if (fullk) {
-    const int grid = std::max(c->n_cu, (w.NRB + 3) / 4);
+    const int grid = fk_grid;
+    if (groups_out) *groups_out = grid;
     const int nrmax = (w.NRB + grid - 1) / grid;
     g.trace = (g.trace && grid <= 1024) ? g.trace : nullptr;
     // QKV: split by half row blocks where that lowers the largest share (3 halves instead of 2 blocks at d = 4096);
     // a run of u halves touches at most u/2 + 1 blocks
     const int umax = (2 * w.NRB + grid - 1) / grid;
-    const bool half = g.epi == EPI_QKV && umax < 2 * nrmax && umax / 2 + 1 <= 2 &&
-                      (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
-    if (half) e = launch_fk<2, true>(g, grid, c->stream);
-    else e = nrmax <= 2 ? launch_fk<2>(g, grid, c->stream) : nrmax == 3 ? launch_fk<3>(g, grid, c->stream) : launch_fk<4>(g, grid, c->stream);
+    const bool half = g.epi == EPI_QKV && umax < 2 * nrmax && umax / 2 + 1 <= 2 && fits_rsrc;
+    if (half) e = launch_fk<2, true>(c, bytes, g, grid);
+    else e = nrmax <= 2 ? launch_fk<2>(c, bytes, g, grid) : nrmax == 3 ? launch_fk<3>(c, bytes, g, grid) : launch_fk<4>(c, bytes, g, grid);
   } else if (c->f32) {
     switch (p.RW) {
-      case 1: e = launch_k2<3, 3, 1, 4>(g, p.lds, c->stream); break;
-      case 2: e = launch_k2<3, 3, 2, 2>(g, p.lds, c->stream); break;
-      default: e = launch_k2<3, 3, 3, 2>(g, p.lds, c->stream); break;
+      case 1: e = launch_k2<3, 3, 1, 4>(c, bytes, g, p.lds); break;
+      case 2: e = launch_k2<3, 3, 2, 2>(c, bytes, g, p.lds); break;
+      default: e = launch_k2<3, 3, 3, 2>(c, bytes, g, p.lds); break;
     }
   } else {
     switch (p.RW) {
-      case 1: e = launch_k2<1, 2, 1, 16>(g, p.lds, c->stream); break;
-      case 2: e = launch_k2<1, 2, 2, 8>(g, p.lds, c->stream); break;
-      default: e = launch_k2<1, 2, 3, 5>(g, p.lds, c->stream); break;
+      case 1: e = launch_k2<1, 2, 1, 16>(c, bytes, g, p.lds); break;
+      case 2: e = launch_k2<1, 2, 2, 8>(c, bytes, g, p.lds); break;
+      default: e = launch_k2<1, 2, 3, 5>(c, bytes, g, p.lds); break;
     }
   }
   if (e != hipSuccess) return fail(EAGLE_EHIP, "fused gemm launch failed: %s", hipGetErrorString(e));
-  if (timed) {
-    HIPCHK(hipEventRecord(c->gemm_ev[c->gemm_ev_used + 1], c->stream));
-    c->gemm_ev_used += 2;
-    c->gemm_ev_bytes.push_back((double)w.N * w.K * c->elt);
-  }
   return EAGLE_OK;
 }
 
@@ -875,7 +913,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   int rc;
   Gemm2 g = gemm2_base(c, pass, M);
   g.epi = EPI_QKV; g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups); g.kv = kv_for(c, li);
-  if ((rc = gemm2(c, w.qkv, c->xf2_d, g, nullptr))) return rc;
+  if ((rc = (c->cur_class = KC_QKV, gemm2(c, w.qkv, c->xf2_d, g, nullptr)))) return rc;
   {
     int n_splits = attn_splits(c, ctx_max + 64, H * pass.n_seq);
     unsigned long long* atrace = (c->attn_no++ == c->attn_trace_sel && n_splits * H <= 1024) ? c->trace : nullptr;
@@ -889,8 +927,9 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
       HIPCHK(hipFuncSetAttribute((const void*)k2_attn<CT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); \
       attr_done = true;                                                                                                 \
     }                                                                                                                   \
-    k2_attn<CT, DH><<<grid, 256, (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, c->stream>>>(                                  \
-        pass, c->tree_d, c->st, kv, c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP, atrace, 1, 1); \
+    hipError_t e_ = launch_k(c, KC_ATTN, attn_bytes(c, pass, n_new), "k2_attn", k2_attn<CT, DH>, grid, dim3(256), (size_t)(4 * DH * 32 + 4 * 2 * 32) * 4, \
+        pass, (const TreeDev*)c->tree_d, c->st, kv, (const float*)c->Q, c->part_o, c->part_ml, H, n_splits, n_new, scale, c->cnt_attn, c->xf2_att, c->NXP, atrace, 1, 1); \
+    if (e_ != hipSuccess) return fail(EAGLE_EHIP, "attention launch failed: %s", hipGetErrorString(e_));                \
   } while (0)
     if (c->kv_f32) { if (dh == 128) ATTN2(float, 128); else if (dh == 64) ATTN2(float, 64); else ATTN2(float, 32); }
     else { if (dh == 128) ATTN2(bf16_t, 128); else if (dh == 64) ATTN2(bf16_t, 64); else ATTN2(bf16_t, 32); }
@@ -899,7 +938,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
   }
   g = gemm2_base(c, pass, M);
   g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = w.mlp_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq1;
-  if ((rc = gemm2(c, w.o, c->xf2_att, g, &c->ssq1_groups))) return rc;
+  if ((rc = (c->cur_class = KC_O, gemm2(c, w.o, c->xf2_att, g, &c->ssq1_groups)))) return rc;
   if (w.moe) {
     // routed experts (see the general path): experts no row selected are skipped on the device (skip_flag)
     const int E = cf.n_experts;
@@ -913,28 +952,28 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
       g = gemm2_base(c, pass, M);
       g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
       g.skip_flag = c->expert_used + e;
-      if ((rc = gemm2(c, w.e_gu[e], c->xf2_d, g, nullptr))) return rc;
+      if ((rc = (c->cur_class = KC_GATEUP, gemm2(c, w.e_gu[e], c->xf2_d, g, nullptr)))) return rc;
       g = gemm2_base(c, pass, M);
       g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = next_gain; g.xf_out = c->xf2_dB; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
       g.row_w = c->moe_w + (size_t)e * 128; g.skip_flag = c->expert_used + e;
-      if ((rc = gemm2(c, w.e_dn[e], c->xf2_ffn, g, &c->ssq2_groups))) return rc;
+      if ((rc = (c->cur_class = KC_DOWN, gemm2(c, w.e_dn[e], c->xf2_ffn, g, &c->ssq2_groups)))) return rc;
     }
     std::swap(c->xf2_d, c->xf2_dB);     // the experts all read the old xf2_d; the new one was built beside it
     return EAGLE_OK;
   }
   g = gemm2_base(c, pass, M);
   g.epi = EPI_SWIGLU; g.in_scale = scale_of(c, c->ssq1, c->ssq1_groups); g.xf_out = c->xf2_ffn; g.xf_KS = F / 16;
-  if ((rc = gemm2(c, w.gu, c->xf2_d, g, nullptr))) return rc;
+  if ((rc = (c->cur_class = KC_GATEUP, gemm2(c, w.gu, c->xf2_d, g, nullptr)))) return rc;
   g = gemm2_base(c, pass, M);
   g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = next_gain; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
-  return gemm2(c, w.dn, c->xf2_ffn, g, &c->ssq2_groups);
+  return (c->cur_class = KC_DOWN, gemm2(c, w.dn, c->xf2_ffn, g, &c->ssq2_groups));
 }
 
 static int lm_head2(eagle_ctx* c, const Pass& pass, int M, bool scaled, float* out, int out_kind, int only_last_row) {
   Gemm2 g = gemm2_base(c, pass, M);
   g.epi = EPI_LOGITS; g.logits = out; g.out_kind = out_kind; g.V = c->cfg.vocab; g.only_last_row = only_last_row;
   if (scaled) g.in_scale = scale_of(c, c->ssq2, c->ssq2_groups);
-  return gemm2(c, c->lm_head, c->xf2_d, g, nullptr);
+  return (c->cur_class = KC_LMHEAD, gemm2(c, c->lm_head, c->xf2_d, g, nullptr));
 }
 
 static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, float* logits_out, int out_kind) {
@@ -965,7 +1004,7 @@ static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new,
   Gemm2 g = gemm2_base(c, pass, M);
   g.epi = EPI_RESID; g.h_in = nullptr; g.h_out = c->h2; g.bias = c->loaded_layer[EAGLE_W_FC_BIAS][0] ? c->fc_bias : nullptr;
   g.gain_next = c->layers[cf.n_layers].attn_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
-  if ((rc = gemm2(c, c->fc, c->xf2_2d, g, &c->ssq2_groups))) return rc;
+  if ((rc = (c->cur_class = KC_FC, gemm2(c, c->fc, c->xf2_2d, g, &c->ssq2_groups)))) return rc;
   if ((rc = layer2(c, pass, M, cf.n_layers, ctx_max, n_new, nullptr))) return rc;
   if (store_rows) {                          // (the draft passes leave this copy to k_expand)
     k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->h2, c->node_f, c->pend_f, c->chunk_f, d);
@@ -1206,9 +1245,15 @@ extern "C" int eagle_step(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, i
   int rc;
   const bool prof = c->prof_mode > 0;
   if (prof) HIPCHK(hipEventRecord(c->ev[0], c->stream));
-  if ((rc = do_draft(c))) return rc;
+  c->cur_phase = 0;
+  rc = do_draft(c);
+  c->cur_phase = -1;
+  if (rc) return rc;
   if (prof) HIPCHK(hipEventRecord(c->ev[1], c->stream));
-  if ((rc = do_verify(c))) return rc;
+  c->cur_phase = 1;
+  rc = do_verify(c);
+  c->cur_phase = -1;
+  if (rc) return rc;
   if (prof) HIPCHK(hipEventRecord(c->ev[2], c->stream));
   if ((rc = do_accept(c))) return rc;
   if (prof) HIPCHK(hipEventRecord(c->ev[3], c->stream));
@@ -1266,7 +1311,6 @@ extern "C" int eagle_vanilla_step(eagle_ctx* c, int32_t* tokens) {
     if (tokens) tokens[s] = tk[s];
   }
   c->phase = 0;
-  if (c->prof_mode == 2) return collect_gemm_events(c);
   return EAGLE_OK;
 }
 
@@ -1432,28 +1476,77 @@ extern "C" int eagle_get_kv_row(eagle_ctx* c, int32_t seq, int32_t layer, int32_
   return EAGLE_OK;
 }
 
+// ---------------------------------------------------------------------------- measurement reference
+// A bare streaming read: every lane loads 16 bytes per instruction, 8 instructions in flight, work-groups walk the
+// buffer grid-strided in 32 KiB pieces; nothing is computed beyond an xor that keeps the loads alive.  What it
+// sustains is the practical ceiling against which the weight-streaming kernels are read.
+__global__ __launch_bounds__(256) void k_stream_read(const u32x4* __restrict__ src, size_t n16, uint32_t* sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * 2048;
+  for (size_t base = (size_t)blockIdx.x * 2048; base < n16; base += stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const size_t i = base + (size_t)u * 256 + threadIdx.x;
+      v[u] = __builtin_nontemporal_load(src + (i < n16 ? i : n16 - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9E3779B9u) *sink = acc;
+}
+
+extern "C" int eagle_probe_stream_read(const void* buf_dev, size_t bytes, int32_t iters, void* hip_stream, double* gb_per_s) {
+  if (!buf_dev || !gb_per_s || ((uintptr_t)buf_dev & 15)) return fail(EAGLE_EINVAL, "buffer must be a 16-byte aligned device pointer");
+  if (bytes < (1u << 20) + 64 || iters < 1 || iters > 1000) return fail(EAGLE_EINVAL, "need at least 1 MiB + 64 bytes and 1..1000 iterations");
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the last 64 bytes of the buffer serve as the (never written) sink
+  const size_t n16 = (bytes - 64) / 16;
+  uint32_t* sink = (uint32_t*)((char*)buf_dev + n16 * 16);
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  HIPCHK(hipEventCreate(&e1));
+  k_stream_read<<<2048, 256, 0, st>>>((const u32x4*)buf_dev, n16, sink);        // warm-up
+  double ms_sum = 0;
+  for (int i = 0; i < iters; ++i) {
+    hipExtLaunchKernelGGL(k_stream_read, dim3(2048), dim3(256), 0, st, e0, e1, 0, (const u32x4*)buf_dev, n16, sink);
+    if (hipGetLastError() != hipSuccess) return fail(EAGLE_EHIP, "probe launch failed");
+    HIPCHK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+    ms_sum += ms;
+  }
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *gb_per_s = (double)n16 * 16.0 * iters / (ms_sum * 1e-3) / 1e9;
+  return EAGLE_OK;
+}
+
 extern "C" int eagle_set_profiling(eagle_ctx* c, int32_t mode) {
   if (!c || mode < 0 || mode > 2) return fail(EAGLE_EINVAL, "mode must be 0, 1 or 2");
   c->prof_mode = mode;
-  if (mode == 2) {
-    // what a pair of events costs with nothing between them: subtracted by callers that want the kernel's own time
-    const int n = 64;
-    if (c->gemm_ev.size() < (size_t)n + 1)
-      for (int i = (int)c->gemm_ev.size(); i < n + 1; ++i) { hipEvent_t e; HIPCHK(hipEventCreate(&e)); c->gemm_ev.push_back(e); }
-    HIPCHK(hipStreamSynchronize(c->stream));
-    for (int i = 0; i <= n; ++i) HIPCHK(hipEventRecord(c->gemm_ev[i], c->stream));
-    HIPCHK(hipStreamSynchronize(c->stream));
-    std::vector<float> gaps(n);                            // the median: a late first record or a stray stall must not move it
-    for (int i = 0; i < n; ++i) HIPCHK(hipEventElapsedTime(&gaps[i], c->gemm_ev[i], c->gemm_ev[i + 1]));
-    std::sort(gaps.begin(), gaps.end());
-    c->event_pair_ms = 0.5 * ((double)gaps[n / 2 - 1] + (double)gaps[n / 2]);
-  }
   return EAGLE_OK;
 }
 extern "C" int eagle_get_profile(eagle_ctx* c, eagle_profile* out, int32_t reset) {
   if (!c || !out) return fail(EAGLE_EINVAL, "null argument");
   *out = c->prof;
-  out->event_pair_ms = c->event_pair_ms;
   if (reset) memset(&c->prof, 0, sizeof(c->prof));
+  return EAGLE_OK;
+}
+extern "C" int eagle_get_kernel_stats(eagle_ctx* c, int32_t phase, eagle_kernel_stat* out, int32_t cap, int32_t* n_out, int32_t reset) {
+  if (!c || !out || !n_out) return fail(EAGLE_EINVAL, "null argument");
+  if (phase != 0 && phase != 1) return fail(EAGLE_EINVAL, "phase must be 0 (drafting) or 1 (verification)");
+  int n = 0;
+  for (int k = 0; k < KC_COUNT; ++k) {
+    KStat& ks = c->kstat[phase][k];
+    if (ks.launches == 0) continue;
+    if (n >= cap) return fail(EAGLE_EINVAL, "room for %d entries is not enough", cap);
+    eagle_kernel_stat& o = out[n++];
+    memset(&o, 0, sizeof(o));
+    snprintf(o.name, sizeof(o.name), "%s", kKernelClassName[k]);
+    snprintf(o.kernel, sizeof(o.kernel), "%s", ks.kernel);
+    o.ms = ks.ms; o.launches = ks.launches; o.bytes = ks.bytes;
+    if (reset) ks = KStat();
+  }
+  *n_out = n;
   return EAGLE_OK;
 }

@@ -676,9 +676,10 @@ __device__ inline float fk_sum(const float* red, int nrmax, int j, int n_local, 
 
 // HALF: the unit of the work split is half a row block (16 weight rows) instead of a whole one, for matrices whose
 // row blocks do not divide evenly over the CUs (QKV at d = 4096: 384 blocks over 256 CUs = 1 or 2 each, but 3 halves
-// each).  A work-group then owns a run of halves; of a block it shares with a neighbour it loads and finishes only
-// its own 16 rows (the other lanes of the tile load nothing and multiply zeros).  Rotate-half pairs are adjacent rows,
-// so a half holds whole pairs; used for the QKV epilogue only.
+// each) and for matrices with fewer row blocks than CUs (O, down, FC at d = 4096: 128 blocks = one half per CU, which
+// keeps them whole-K: no partial sums are exchanged).  A work-group then owns a run of halves; of a block it shares
+// with a neighbour it loads and finishes only its own 16 rows (the other lanes of the tile load nothing and multiply
+// zeros).  Rotate-half pairs are adjacent rows, so a half holds whole pairs.  Epilogues: QKV and the residual one.
 template <int NWP, int NXP, int NRMAX, bool HALF = false>
 __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -787,6 +788,38 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
         if (g.kv_f32) { ((float*)base)[off + d1] = a; ((float*)base)[off + d2] = b; }
         else { ((bf16_t*)base)[off + d1] = f32_to_bf16(a); ((bf16_t*)base)[off + d2] = f32_to_bf16(b); }
       }
+    }
+  } else if (g.epi == EPI_RESID) {
+    // h_out = h_in + (routing weight *) W x + bias on this work-group's rows [n_lo, n_hi); per-token partial sums of
+    // squares for the consumer's RMSNorm; x * gain of the next norm in fragment layout.  One output per thread and
+    // round, parked in LDS behind `red`, then repacked in runs of 8 rows.
+    float* xo = red + (size_t)8 * NRMAX * 16 * 64;              // [rows <= 32*NRMAX][33]
+    const int n_lo = HALF ? rb0 * 32 + row_lo : rb0 * 32;
+    const int n_hi = min(HALF ? (rb1 - 1) * 32 + row_hi : rb1 * 32, g.N);
+    const float rw = g.row_w ? g.row_w[m] : 1.0f;
+    float ss = 0.f;
+    for (int nl = slot; nl < n_hi - n_lo; nl += 16) {
+      const int n = n_lo + nl;
+      float v = fk_sum(red, NRMAX, (n >> 5) - rb0, n & 31, m);
+      if (g.row_w) v *= rw;
+      if (g.bias) v += g.bias[n];
+      if (g.h_in && live) v += g.h_in[(size_t)m * g.d + n];
+      if (live) g.h_out[(size_t)m * g.d + n] = v;
+      ss += v * v;
+      xo[nl * 33 + m] = g.gain_next ? v * g.gain_next[n] : v;
+    }
+    sh_small[slot * 32 + m] = ss;
+    __syncthreads();
+    if (threadIdx.x < 32 && g.ssq_out) {
+      float a = 0.f;
+      for (int i = 0; i < 16; ++i) a += sh_small[i * 32 + threadIdx.x];
+      g.ssq_out[blockIdx.x * 32 + threadIdx.x] = a;
+    }
+    for (int c = slot; c < (n_hi - n_lo + 7) >> 3; c += 16) {
+      float x[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] = 8 * c + t < n_hi - n_lo ? xo[(8 * c + t) * 33 + m] : 0.f;
+      if (live) xf_store8(g.xf_out, m, n_lo + 8 * c, 1, g.xf_KS, NXP, x);
     }
   } else {                                                      // EPI_LOGITS
     const int nend = min(g.N, g.V);
