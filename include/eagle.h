@@ -169,12 +169,16 @@ enum {
   EAGLE_BUF_VANILLA_LOGITS,    /* fp32 [vocab]              logits of the last eagle_vanilla_step / prefill */
   EAGLE_BUF_STATE,             /* int32 [4]: committed tokens, cached target positions, pending features, steps */
   EAGLE_BUF_KV_ROW,            /* see eagle_get_kv_row                                                      */
-  EAGLE_BUF_GEMM_TRACE         /* profiling builds of the library (-DEAGLE_TRACE) only, all zero otherwise:
+  EAGLE_BUF_GEMM_TRACE,        /* profiling builds of the library (-DEAGLE_TRACE) only, all zero otherwise:
                                   uint64 [1024 work-groups][8 events], 100 MHz time stamps of ONE launch of the
                                   weight-streaming GEMM kernel, selected with the environment variable
                                   EAGLE_GEMM_TRACE=<index of the launch within the verify phase> (read by eagle_init);
                                   events: 0 entered, 1 activations staged, 2 weight stream done, 3 partial sums
                                   published, 4 epilogue done (the work-groups that ran one). */
+  EAGLE_BUF_PREFILL_FEATURES   /* fp32 [rows, d_model]: target features of the rows of the most recent prompt pass of
+                                  eagle_prefill (the whole prompt when it fits one pass: 512 rows for dense bf16
+                                  models, 128 otherwise; else its last pass) -- Sec. 3.1: what the head's prompt
+                                  pass consumes */
 };
 int eagle_get_buffer(eagle_ctx *ctx, int32_t which, int32_t seq, void *host_dst, size_t cap_bytes);
 /* K and V (fp32, [n_kv_heads*head_dim] each) of target layer `layer` (or EAGLE_HEAD_LAYER) at cache position pos. */

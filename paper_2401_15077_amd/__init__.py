@@ -19,7 +19,7 @@ HEAD_LAYER = -1
 (W_EMBED, W_LM_HEAD, W_FINAL_NORM, W_FC, W_FC_BIAS, W_ATTN_NORM, W_Q, W_K, W_V, W_O, W_MLP_NORM, W_ROUTER,
  W_GATE, W_UP, W_DOWN) = range(15)
 (BUF_LOGITS, BUF_FEATURES, BUF_DRAFT_LOGITS, BUF_DRAFT_FEATURES, BUF_TREE_TOKENS, BUF_TOKENS, BUF_VANILLA_LOGITS,
- BUF_STATE, BUF_KV_ROW, BUF_GEMM_TRACE) = range(10)
+ BUF_STATE, BUF_KV_ROW, BUF_GEMM_TRACE, BUF_PREFILL_FEATURES) = range(11)
 
 _LAYER_IDS = {"attn_norm": W_ATTN_NORM, "wq": W_Q, "wk": W_K, "wv": W_V, "wo": W_O, "mlp_norm": W_MLP_NORM,
               "router": W_ROUTER, "gate": W_GATE, "up": W_UP, "down": W_DOWN}
@@ -229,6 +229,8 @@ class Eagle:
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         first = ctypes.c_int32()
         self._chk(self.lib.eagle_prefill(self.h, seq, _p32(p), len(p), ctypes.byref(first)))
+        chunk = 512 if (self.shape.dtype == "bf16" and self.shape.n_experts == 0) else 128
+        self.last_prefill_rows = (len(p) - 1) % chunk + 1          # rows of the prompt's last pass
         self.n_active = max(self.n_active, seq + 1)
         return int(first.value)
 
@@ -327,6 +329,9 @@ class Eagle:
             out = np.empty(n, np.int32)
         elif which == BUF_GEMM_TRACE:
             out = np.zeros((1024, 8), np.uint64)
+        elif which == BUF_PREFILL_FEATURES:
+            rows = self.last_prefill_rows
+            out = np.empty((rows, d), np.float32)
         else:
             raise ValueError(which)
         self._chk(self.lib.eagle_get_buffer(self.h, which, seq, out.ctypes.data, out.nbytes))

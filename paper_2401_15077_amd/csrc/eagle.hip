@@ -81,6 +81,8 @@ struct eagle_ctx {
   int NWP, NXP, elt, kv_elt;         // weight planes, activation planes, bytes per weight / per KV element
   TreeDev tree_h; TreeDev* tree_d;
   int M, D, Mmax, max_level_rows;
+  int last_chunk_rows = 0, last_chunk_start = 0;   // rows of the most recent prompt pass of the target (their features stay in chunk_f)
+  int pf_chunk = EAGLE_PREFILL_CHUNK;   // rows of one prompt pass: 512 where the large-M GEMM exists (bf16, dense), else 128
   // weights
   void* embed; PackedW lm_head, fc; float *final_norm, *fc_bias;
   std::vector<LayerW> layers;        // [n_layers] target + [1] head
@@ -131,6 +133,19 @@ static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
   p.ks_per_split = (KS + S - 1) / S;
   p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
   p.chunk = std::max(1, 64 / (NXP * MT));
+  return p;
+}
+
+// Work split of the large-M GEMM (k_gemm_pf): work-group tiles of 8 row blocks x 4 row tiles; K is split only when the
+// tiles alone would leave most CUs idle (narrow matrices: O, down), since every split writes and re-reads M x N floats.
+static GemmPlan plan_pf(int NRB, int KS, int MT, int n_cu) {
+  GemmPlan p;
+  const int wgs = ((NRB + 7) / 8) * ((MT + 3) / 4);
+  int S = wgs * 2 > n_cu ? 1 : std::min(4, n_cu / std::max(1, wgs));
+  S = std::max(1, std::min(S, KS / 32));
+  p.ks_per_split = ((KS + S - 1) / S + 3) / 4 * 4;
+  p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
+  p.chunk = 4;
   return p;
 }
 
@@ -294,7 +309,7 @@ static size_t layout(eagle_ctx* c) {
   c->pend_f = a.take<float>((size_t)B * D1 * d);
   c->node_f = a.take<float>((size_t)B * M * d);
   c->F = a.take<float>((size_t)B * M * d);
-  c->chunk_f = a.take<float>((size_t)EAGLE_PREFILL_CHUNK * d);
+  c->chunk_f = a.take<float>((size_t)c->pf_chunk * d);
   c->featbuf = a.take<float>((size_t)c->Mmax * d);
   c->draft_logits = a.take<float>((size_t)B * M * V);
   c->L = a.take<float>((size_t)B * M * V);
@@ -316,7 +331,7 @@ static size_t layout(eagle_ctx* c) {
   size_t worst = 0;
   auto consider = [&](const PackedW& w) {
     for (int mt = 1; mt <= MTm; ++mt) {
-      GemmPlan p = plan_gemm(w.NRB, w.KS, c->NXP, mt);
+      GemmPlan p = mt > 4 ? plan_pf(w.NRB, w.KS, mt, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, mt);
       worst = std::max(worst, (size_t)p.S * w.Npad * (size_t)(mt * 32));
     }
   };
@@ -384,9 +399,10 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   c->M = c->tree_h.M; c->D = c->tree_h.D;
   c->max_level_rows = 1;
   for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
-  int rows = std::max(EAGLE_PREFILL_CHUNK, cfg->max_batch * c->M);
+  if (cfg->max_batch * c->M > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
+  c->pf_chunk = (!c->f32 && cfg->n_experts == 0) ? 512 : EAGLE_PREFILL_CHUNK;
+  int rows = std::max(c->pf_chunk, cfg->max_batch * c->M);
   c->Mmax = (rows + 31) / 32 * 32;
-  if (c->Mmax > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
   return EAGLE_OK;
 }
 
@@ -604,11 +620,20 @@ static hipError_t launch_gemm_mt(eagle_ctx* c, const PackedW& w, const bf16_t* X
 
 // PT <- X (XF layout, MT row tiles) times W^T.  Returns the split count through *S.
 static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S) {
-  GemmPlan p = plan_gemm(w.NRB, w.KS, c->NXP, MT);
+  const bool big = MT > 4;
+  GemmPlan p = big ? plan_pf(w.NRB, w.KS, MT, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, MT);
   if ((size_t)p.S * w.Npad * MT * 32 > c->pt_floats) return fail(EAGLE_EINVAL, "internal: partial buffer too small");
-  if (MT < 1 || MT > 4) return fail(EAGLE_EINVAL, "internal: MT out of range");
+  if (MT < 1 || MT * 32 > c->Mmax || (big && c->f32)) return fail(EAGLE_EINVAL, "internal: MT out of range");
   *S = p.S;
-  hipError_t e = c->f32 ? launch_gemm_mt<3, 3>(c, w, XF, c->PT, MT, p) : launch_gemm_mt<1, 2>(c, w, XF, c->PT, MT, p);
+  hipError_t e;
+  if (big) {
+    static bool attr_set = false;
+    if (!attr_set) { HIPCHK(hipFuncSetAttribute((const void*)k_gemm_pf<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_set = true; }
+    const int MQ = (MT + 3) / 4, G = ((w.NRB + 7) / 8) * p.S;
+    const int grid = (G + 7) / 8 * 8 * MQ;
+    e = launch_k(c, c->cur_class, (double)w.N * w.K * c->elt, "k_gemm_pf", k_gemm_pf<2>, dim3(grid), dim3(256), (size_t)64 * 1024,
+                 (const bf16_t*)w.w, XF, c->PT, w.NRB, w.KS, p.ks_per_split, p.S, w.Npad, MT);
+  } else e = c->f32 ? launch_gemm_mt<3, 3>(c, w, XF, c->PT, MT, p) : launch_gemm_mt<1, 2>(c, w, XF, c->PT, MT, p);
   if (e != hipSuccess) return fail(EAGLE_EHIP, "gemm launch failed: %s", hipGetErrorString(e));
   return EAGLE_OK;
 }
@@ -1043,9 +1068,10 @@ extern "C" int eagle_prefill(eagle_ctx* c, int32_t seq, const int32_t* prompt, i
   int zero = 0;
   HIPCHK(hipMemcpyAsync(c->st.ctx_len + seq, &zero, 4, hipMemcpyHostToDevice, c->stream));
   HIPCHK(hipStreamSynchronize(c->stream));   // `zero` and `prompt` are host memory of the caller
-  for (int start = 0; start < n; start += EAGLE_PREFILL_CHUNK) {
-    const int cn = std::min(EAGLE_PREFILL_CHUNK, n - start);
+  for (int start = 0; start < n; start += c->pf_chunk) {
+    const int cn = std::min(c->pf_chunk, n - start);
     const bool last = start + cn == n;
+    c->last_chunk_rows = cn; c->last_chunk_start = start;
     Pass pt{PASS_PREFILL_T, cn, 1, seq, 0, start, cn};
     if ((rc = target_forward(c, pt, start + cn, cn, last, c->vanilla_logits, 1, 1))) return rc;
     if (last) {
@@ -1450,6 +1476,7 @@ extern "C" int eagle_get_buffer(eagle_ctx* c, int32_t which, int32_t seq, void* 
       return EAGLE_OK;
     }
     case EAGLE_BUF_GEMM_TRACE: src = c->trace; bytes = (size_t)1024 * 8 * 8; break;
+    case EAGLE_BUF_PREFILL_FEATURES: src = c->chunk_f; bytes = (size_t)c->last_chunk_rows * g.d_model * 4; break;
     default: return fail(EAGLE_EINVAL, "unknown buffer id %d", which);
   }
   if (cap < bytes) return fail(EAGLE_EINVAL, "destination of %zu bytes is smaller than the %zu needed", cap, bytes);

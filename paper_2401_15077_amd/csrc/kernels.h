@@ -301,6 +301,118 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, siz
   }
 }
 
+// ============================================================================ large-M GEMM (prompt passes of up to 512 rows)
+// Same operands and the same PT[s][m][n] result as k_gemm, for passes whose rows fill several 128-row tiles: here the
+// MFMA pipes, not the weight stream, are the bound (Sec. 3.1: the head consumes the whole prompt's features, so the
+// prompt runs through the target and the head once, as one large matrix product per weight matrix).
+//   work-group tile  256 weight rows (8 row blocks) x 128 activation rows (4 row tiles), 4 waves;
+//   wave w           row blocks 2w, 2w+1 x all 4 activation tiles: 8 accumulator tiles, 16 MFMAs per k-step
+//   activations      the tile's 2 planes x 4 row tiles pass through LDS in chunks of CH k-steps, double-buffered; the
+//                    next chunk travels global -> registers while the current one is multiplied (one barrier a chunk)
+//   weights          each wave streams its own two row blocks global -> registers one chunk ahead
+// Work-groups that share a weight tile (the activation-row tiles of one weight-row tile) get ids 8 apart, i.e. the same
+// XCD under round-robin dispatch, next to each other in dispatch order: the tile comes from HBM once and from that
+// XCD's L2 afterwards.
+template <int NXP>
+__global__ __launch_bounds__(256) void k_gemm_pf(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ XF,
+                                                 float* __restrict__ PT, int NRB, int KS, int ks_per_split, int S, int Npad,
+                                                 int MT /*32-row tiles of the pass*/) {
+  constexpr int CH = 4;                                         // k-steps per LDS stage
+  constexpr int XT = NXP * 4 * CH;                              // activation tiles (1 KiB) per stage
+  constexpr int XR = XT * 64 / 256;                             // 16-byte pieces per thread and stage
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* xs = (u32x4*)smem;                                     // [2 stages][NXP*4 tiles][CH][64]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int MQ = (MT + 3) >> 2, NT = (NRB + 7) >> 3, G = NT * S;
+  // id -> (group = (weight-row tile, split), activation-row tile)
+  const int L = blockIdx.x, blk = L / (8 * MQ), rem = L % (8 * MQ), mq = rem >> 3, g = blk * 8 + (rem & 7);
+  if (g >= G) return;
+  const int nt = g / S, s = g % S;
+  const int rbA = min(nt * 8 + 2 * wave, NRB - 1), rbB = min(nt * 8 + 2 * wave + 1, NRB - 1);
+  const bool liveA = nt * 8 + 2 * wave < NRB, liveB = nt * 8 + 2 * wave + 1 < NRB;
+  const int k_begin = s * ks_per_split, k_end = min(KS, k_begin + ks_per_split);
+  if (k_end <= k_begin) return;
+  const int klast = k_end - 1;
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.f;
+  const u32x4* wA = (const u32x4*)(Wp + (size_t)rbA * KS * 512) + lane;
+  const u32x4* wB = (const u32x4*)(Wp + (size_t)rbB * KS * 512) + lane;
+  u32x4 xr[XR], ar[CH][2];
+  // piece i of a stage: tile pm = i / (CH*64) (= plane*4 + row tile), k-step (i / 64) % CH, lane chunk i % 64
+  auto load_x = [&](int c0) {
+#pragma unroll
+    for (int u = 0; u < XR; ++u) {
+      const int i = u * 256 + (int)threadIdx.x;
+      const int pm = i / (CH * 64), kk = (i / 64) % CH, l = i & 63;
+      const int plane = pm >> 2, mt = min(mq * 4 + (pm & 3), MT - 1);
+      xr[u] = *((const u32x4*)(XF + (((size_t)plane * MT + mt) * KS + min(c0 + kk, klast)) * 512) + l);
+    }
+  };
+  auto load_a = [&](int c0) {
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const size_t ko = (size_t)min(c0 + u, klast) * 64;
+      ar[u][0] = wA[ko]; ar[u][1] = wB[ko];
+    }
+  };
+  auto store_x = [&](int stage) {
+#pragma unroll
+    for (int u = 0; u < XR; ++u) xs[(size_t)stage * XT * 64 + u * 256 + threadIdx.x] = xr[u];
+  };
+  load_x(k_begin);
+  load_a(k_begin);
+  store_x(0);
+  __syncthreads();
+  int stage = 0;
+  for (int c0 = k_begin; c0 < k_end; c0 += CH, stage ^= 1) {
+    const int nk = min(CH, k_end - c0);
+    const bool more = c0 + CH < k_end;
+    u32x4 a[CH][2];
+#pragma unroll
+    for (int u = 0; u < CH; ++u) { a[u][0] = ar[u][0]; a[u][1] = ar[u][1]; }
+    if (more) { load_x(c0 + CH); load_a(c0 + CH); }             // in flight while this stage is multiplied
+    const u32x4* xb = xs + (size_t)stage * XT * 64;
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      if (u < nk) {
+#pragma unroll
+        for (int q = 0; q < NXP; ++q)
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const u32x4 b = xb[((size_t)(q * 4 + t) * CH + u) * 64 + lane];
+            acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][0]), __builtin_bit_cast(bf16x8, b), acc[0][t], 0, 0, 0);
+            acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][1]), __builtin_bit_cast(bf16x8, b), acc[1][t], 0, 0, 0);
+          }
+      }
+    }
+    if (more) store_x(stage ^ 1);                               // the other stage was last read before the previous barrier
+    __syncthreads();
+  }
+  // accumulator register r of lane l: weight row 8*(r/4) + 4*(l/32) + r%4, activation row l%32; PT[s][m][n], n fastest
+  const int Mpad = MT * 32;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    if (!(j ? liveB : liveA)) continue;
+    const int rb = j ? rbB : rbA;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int mt = mq * 4 + t;
+      if (mt >= MT) continue;
+      float* out = PT + ((size_t)s * Mpad + mt * 32 + (lane & 31)) * Npad + (size_t)rb * 32 + 4 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        f32x4 v; v.x = acc[j][t][4 * i]; v.y = acc[j][t][4 * i + 1]; v.z = acc[j][t][4 * i + 2]; v.w = acc[j][t][4 * i + 3];
+        *(f32x4*)(out + 8 * i) = v;
+      }
+    }
+  }
+}
+
 // ============================================================================ row producers
 // h[r][:] = embedding of row r's token (fp32).  EmbT = float or bf16_t.
 template <typename EmbT>

@@ -33,6 +33,10 @@ def check_prefill(eng, orc, prompt, tol, margin_thr=2e-2, seq=0):
     lg = eng.get_buffer(pkg.BUF_VANILLA_LOGITS, seq)
     err = float(np.abs(lg - orc.prefill_logits[-1]).max())
     assert err <= tol, f"prefill logits differ by {err}"
+    # the features of every row of the prompt's last pass (the whole prompt when it fits one pass)
+    pf = eng.get_buffer(pkg.BUF_PREFILL_FEATURES, seq)
+    ferr = float(np.abs(pf - orc.prefill_features[len(prompt) - pf.shape[0]:]).max())
+    assert ferr <= tol, f"prefill features differ by {ferr}"
     if first_g != first_o:
         if orc.T == 0.0:
             lo = orc.prefill_logits[-1]
