@@ -400,7 +400,8 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   c->max_level_rows = 1;
   for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
   if (cfg->max_batch * c->M > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
-  c->pf_chunk = (!c->f32 && cfg->n_experts == 0) ? 512 : EAGLE_PREFILL_CHUNK;
+  // (the large-M GEMM walks K in stages of 4 k-steps: every K of the model must be a multiple of 64)
+  c->pf_chunk = (!c->f32 && cfg->n_experts == 0 && cfg->d_ffn % 64 == 0 && (cfg->n_heads * cfg->head_dim) % 64 == 0) ? 512 : EAGLE_PREFILL_CHUNK;
   int rows = std::max(c->pf_chunk, cfg->max_batch * c->M);
   c->Mmax = (rows + 31) / 32 * 32;
   return EAGLE_OK;

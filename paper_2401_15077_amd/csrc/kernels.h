@@ -314,12 +314,12 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, siz
 // XCD under round-robin dispatch, next to each other in dispatch order: the tile comes from HBM once and from that
 // XCD's L2 afterwards.
 template <int NXP>
-__global__ __launch_bounds__(256) void k_gemm_pf(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ XF,
+__global__ __launch_bounds__(256, 2) void k_gemm_pf(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ XF,
                                                  float* __restrict__ PT, int NRB, int KS, int ks_per_split, int S, int Npad,
                                                  int MT /*32-row tiles of the pass*/) {
   constexpr int CH = 4;                                         // k-steps per LDS stage
   constexpr int XT = NXP * 4 * CH;                              // activation tiles (1 KiB) per stage
-  constexpr int XR = XT * 64 / 256;                             // 16-byte pieces per thread and stage
+  constexpr int XR = XT / CH;                                   // activation tiles per stage and k-step = loads per wave and stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* xs = (u32x4*)smem;                                     // [2 stages][NXP*4 tiles][CH][64]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -343,15 +343,19 @@ __global__ __launch_bounds__(256) void k_gemm_pf(const bf16_t* __restrict__ Wp, 
   const u32x4* wA = (const u32x4*)(Wp + (size_t)rbA * KS * 512) + lane;
   const u32x4* wB = (const u32x4*)(Wp + (size_t)rbB * KS * 512) + lane;
   u32x4 xr[XR], ar[CH][2];
-  // piece i of a stage: tile pm = i / (CH*64) (= plane*4 + row tile), k-step (i / 64) % CH, lane chunk i % 64
+  // Activations: global -> registers at the start of a stage, registers -> LDS at its end (the loads have the whole
+  // stage to arrive).  Load u of wave w carries tile u (= plane * 4 + row tile) of k-step c0 + w, which is piece
+  // (u * CH + w) * 64 + lane of the stage.  Every k range is a multiple of CH (host).
   auto load_x = [&](int c0) {
 #pragma unroll
     for (int u = 0; u < XR; ++u) {
-      const int i = u * 256 + (int)threadIdx.x;
-      const int pm = i / (CH * 64), kk = (i / 64) % CH, l = i & 63;
-      const int plane = pm >> 2, mt = min(mq * 4 + (pm & 3), MT - 1);
-      xr[u] = *((const u32x4*)(XF + (((size_t)plane * MT + mt) * KS + min(c0 + kk, klast)) * 512) + l);
+      const int plane = u >> 2, mt = min(mq * 4 + (u & 3), MT - 1);
+      xr[u] = *((const u32x4*)(XF + (((size_t)plane * MT + mt) * KS + min(c0 + wave, klast)) * 512) + lane);
     }
+  };
+  auto store_x = [&](int stage) {
+#pragma unroll
+    for (int u = 0; u < XR; ++u) xs[(size_t)stage * XT * 64 + (size_t)(u * CH + wave) * 64 + lane] = xr[u];
   };
   auto load_a = [&](int c0) {
 #pragma unroll
@@ -360,38 +364,45 @@ __global__ __launch_bounds__(256) void k_gemm_pf(const bf16_t* __restrict__ Wp, 
       ar[u][0] = wA[ko]; ar[u][1] = wB[ko];
     }
   };
-  auto store_x = [&](int stage) {
-#pragma unroll
-    for (int u = 0; u < XR; ++u) xs[(size_t)stage * XT * 64 + u * 256 + threadIdx.x] = xr[u];
-  };
   load_x(k_begin);
   load_a(k_begin);
   store_x(0);
   __syncthreads();
   int stage = 0;
   for (int c0 = k_begin; c0 < k_end; c0 += CH, stage ^= 1) {
-    const int nk = min(CH, k_end - c0);
-    const bool more = c0 + CH < k_end;
-    u32x4 a[CH][2];
+    // the next stage's activations, in flight while this stage is multiplied (issued unconditionally -- k-steps are
+    // clamped to the last one -- so that the number of loads in flight is the same on every path and the compiler's
+    // waits name exactly the load they need)
+    load_x(c0 + CH);
+    const u32x4* xb = xs + (size_t)stage * XT * 64 + lane;
+    u32x4 bq[2][NXP * 4];                                       // the k-step being multiplied and the one after it
 #pragma unroll
-    for (int u = 0; u < CH; ++u) { a[u][0] = ar[u][0]; a[u][1] = ar[u][1]; }
-    if (more) { load_x(c0 + CH); load_a(c0 + CH); }             // in flight while this stage is multiplied
-    const u32x4* xb = xs + (size_t)stage * XT * 64;
+    for (int i = 0; i < NXP * 4; ++i) bq[0][i] = xb[(size_t)(i * CH) * 64];
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      if (u < nk) {
+      if (u + 1 < CH) {
 #pragma unroll
-        for (int q = 0; q < NXP; ++q)
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const u32x4 b = xb[((size_t)(q * 4 + t) * CH + u) * 64 + lane];
-            acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][0]), __builtin_bit_cast(bf16x8, b), acc[0][t], 0, 0, 0);
-            acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][1]), __builtin_bit_cast(bf16x8, b), acc[1][t], 0, 0, 0);
-          }
+        for (int i = 0; i < NXP * 4; ++i) bq[(u + 1) & 1][i] = xb[(size_t)(i * CH + u + 1) * 64];
       }
+#pragma unroll
+      for (int i = 0; i < NXP * 4; ++i) {
+        const int t = i & 3;
+        acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ar[u][0]), __builtin_bit_cast(bf16x8, bq[u & 1][i]), acc[0][t], 0, 0, 0);
+        acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ar[u][1]), __builtin_bit_cast(bf16x8, bq[u & 1][i]), acc[1][t], 0, 0, 0);
+      }
+      // use a slot, refill that slot: the weight tiles of the same k-step of the NEXT stage
+      const size_t ko = (size_t)min(c0 + CH + u, klast) * 64;
+      ar[u][0] = wA[ko]; ar[u][1] = wB[ko];
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) store_x(stage ^ 1);                               // the other stage was last read before the previous barrier
-    __syncthreads();
+    store_x(stage ^ 1);                                         // the other stage was last read before the previous barrier
+    // A bare s_barrier behind a wait for this wave's LDS writes only: __syncthreads() carries a work-group fence, for
+    // which the compiler drains EVERY outstanding load -- the weight refills issued a moment ago included -- once per
+    // stage, which halves the MFMA rate.  All LDS reads of this stage were consumed by the MFMAs above.
+    __builtin_amdgcn_s_waitcnt(0xC07F);                         // lgkmcnt(0); vmcnt and expcnt left alone
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   }
   // accumulator register r of lane l: weight row 8*(r/4) + 4*(l/32) + r%4, activation row l%32; PT[s][m][n], n fastest
   const int Mpad = MT * 32;
