@@ -54,6 +54,7 @@ def main() -> int:
     ap.add_argument("--kv-dtype", default="fp32", choices=["fp32", "bf16"], help="storage type of the KV cache (the default, fp32, is what the parity tests of the bf16 configurations use)")
     ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (each with its own prompt and knob)")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic tree acceptance, no knob (natural acceptance)")
+    ap.add_argument("--weight-bits", type=int, default=16, choices=[16, 4], help="4: the library quantises the weight matrices to 4 bits as it loads them (the paper's int4 case study); algorithmic bytes are then counted at 0.5 B per weight plus the group scales")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=3)
     ap.add_argument("--cpu-prompt", type=int, default=48)
@@ -81,7 +82,8 @@ def main() -> int:
     B = args.batch
     stochastic = args.temperature > 0.0
     t0 = time.time()
-    eng = pkg.Eagle(shape, par, rk, max_batch=B, max_seq=max_seq, temperature=args.temperature, seed=args.seed, kv_dtype=args.kv_dtype)
+    eng = pkg.Eagle(shape, par, rk, max_batch=B, max_seq=max_seq, temperature=args.temperature, seed=args.seed, kv_dtype=args.kv_dtype,
+                    weight_bits=args.weight_bits)
     eng.load_weights(synth.iter_weights(shape, args.seed, synth.device_fmt(shape)))
     t_load = time.time() - t0
     prompts = [synth.prompt(args.seed + 1000 * b, args.prompt, shape.vocab) for b in range(B)]
@@ -213,7 +215,7 @@ def main() -> int:
     # the counter reads for a copy of known size): taken from the committed summary under profiles/, which names the
     # commit it was measured on; only quoted for the workload it was measured on
     default_workload = (args.shape == "llama2-7b" and not args.layers and args.tree == "T26" and args.prompt == 512
-                        and B == 1 and not stochastic and args.kv_dtype == "fp32")
+                        and B == 1 and not stochastic and args.kv_dtype == "fp32" and args.weight_bits == 16)
     traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_llama2-7b_bs1_T26.txt")
     if default_workload and dominant and os.path.exists(tpath):
@@ -227,7 +229,7 @@ def main() -> int:
         "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{shape.name} bs={B} prompt={args.prompt} tree={args.tree}({M} nodes, depth {D}) "
+        "config": {"workload": f"{shape.name}{' int4 weights' if args.weight_bits == 4 else ''} bs={B} prompt={args.prompt} tree={args.tree}({M} nodes, depth {D}) "
                                + (f"temperature {args.temperature} (Alg. 1), no knob" if stochastic else f"greedy knob alpha={alpha:.4f}"),
                    "global_batch": B, "seq_len": args.prompt,
                    "n_layers": shape.n_layers},
@@ -250,7 +252,7 @@ def main() -> int:
     del eng
     torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline and B == 1 and not stochastic:
+    if not args.no_cpu_baseline and B == 1 and not stochastic and args.weight_bits == 16:
         from oracle.eagle_oracle import Oracle
         cp = args.cpu_prompt
         Wo = synth.make_weights(shape, args.seed, synth.oracle_fmt(shape))

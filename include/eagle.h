@@ -54,6 +54,13 @@ typedef struct {
   const int32_t *parent, *rank;
   float temperature;                  /* 0 = greedy */
   uint64_t seed;                      /* counter-based generator for the non-greedy draws */
+  int32_t weight_bits;                /* 0 or 16: weight matrices stay in `dtype`.  4: eagle_load_weight quantises every
+                                         weight matrix of the layers, the head's FC and the LM head (not the embedding)
+                                         to 4 bits as it copies it (Sec. 4.2: the int4 case study) -- weight-only,
+                                         symmetric, per output row and group of 128 input columns: scale = bf16(max|w| / 7),
+                                         code = clip(rint(w / scale), -8, 7), value scale * code.  Needs a dense bf16
+                                         model whose widths are multiples of 128, and at most 32 rows per pass
+                                         (max_batch * n_nodes <= 32); the prompt then runs 32 rows at a time. */
 } eagle_config;
 
 /* Which tensor eagle_load_weight() is given.  Matrices are row-major [out_features, in_features] in the

@@ -41,7 +41,7 @@ class EagleConfig(ctypes.Structure):
                 ("rope_theta", ctypes.c_float), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
                 ("page_tokens", ctypes.c_int32), ("n_nodes", ctypes.c_int32),
                 ("parent", ctypes.POINTER(ctypes.c_int32)), ("rank", ctypes.POINTER(ctypes.c_int32)),
-                ("temperature", ctypes.c_float), ("seed", ctypes.c_uint64)]
+                ("temperature", ctypes.c_float), ("seed", ctypes.c_uint64), ("weight_bits", ctypes.c_int32)]
 
 
 class EagleProfile(ctypes.Structure):
@@ -116,7 +116,7 @@ def _p32(a: Optional[np.ndarray]):
 
 
 def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
-                kv_dtype="fp32"):
+                kv_dtype="fp32", weight_bits=16):
     parent = np.ascontiguousarray(parent, dtype=np.int32)
     rank = np.ascontiguousarray(rank, dtype=np.int32)
     cfg = EagleConfig(dtype=EAGLE_F32 if shape.dtype == "fp32" else EAGLE_BF16,
@@ -125,7 +125,8 @@ def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=6
                       head_dim=shape.head_dim, d_ffn=shape.d_ffn, vocab=shape.vocab, n_experts=shape.n_experts,
                       experts_per_tok=shape.experts_per_tok, draft_moe=int(shape.draft_moe), rms_eps=shape.rms_eps,
                       rope_theta=shape.rope_theta, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
-                      n_nodes=len(parent), parent=_p32(parent), rank=_p32(rank), temperature=temperature, seed=seed)
+                      n_nodes=len(parent), parent=_p32(parent), rank=_p32(rank), temperature=temperature, seed=seed,
+                      weight_bits=weight_bits)
     cfg._keep = (parent, rank)
     return cfg
 
@@ -146,7 +147,7 @@ class Eagle:
     """One libeagle context on cuda:0 (ROCm).  Methods are the C calls, with numpy in/out."""
 
     def __init__(self, shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
-                 kv_dtype="fp32", device="cuda:0"):
+                 kv_dtype="fp32", weight_bits=16, device="cuda:0"):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -154,7 +155,8 @@ class Eagle:
             raise RuntimeError("libeagle needs a GPU (no CPU fallback exists)")
         self.shape, self.device = shape, torch.device(device)
         self.cfg = make_config(shape, parent, rank, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
-                               temperature=temperature, seed=seed, kv_dtype=kv_dtype)
+                               temperature=temperature, seed=seed, kv_dtype=kv_dtype, weight_bits=weight_bits)
+        self.weight_bits = weight_bits
         self.M = len(parent)
         depth = [0] * self.M
         for v in range(1, self.M):
@@ -230,6 +232,8 @@ class Eagle:
         first = ctypes.c_int32()
         self._chk(self.lib.eagle_prefill(self.h, seq, _p32(p), len(p), ctypes.byref(first)))
         chunk = 512 if (self.shape.dtype == "bf16" and self.shape.n_experts == 0) else 128
+        if self.weight_bits == 4:
+            chunk = 32
         self.last_prefill_rows = (len(p) - 1) % chunk + 1          # rows of the prompt's last pass
         self.n_active = max(self.n_active, seq + 1)
         return int(first.value)

@@ -45,6 +45,10 @@ struct PackedW {            // a weight matrix in tiled layout
   bf16_t* w = nullptr;
   size_t plane_stride = 0;  // elements between planes
   int N = 0, Npad = 0, NRB = 0, K = 0, KS = 0;
+  bool q4 = false;          // 4-bit codes (w) + bf16 group scales (sc), see k_pack_weight_q4
+  bf16_t* sc = nullptr;
+  int NG = 0;
+  double bytes(int elt) const { return q4 ? (double)N * K * 0.5 + (double)N * NG * 2.0 : (double)N * K * elt; }   // as stored
 };
 struct LayerW {
   PackedW qkv, o, gu, dn;
@@ -77,7 +81,7 @@ struct eagle_ctx {
   eagle_config cfg;
   hipStream_t stream;
   char* ws; size_t ws_bytes;
-  bool f32, kv_f32;
+  bool f32, kv_f32, q4 = false;      // q4: weight matrices stored in 4 bits (fast path only)
   int NWP, NXP, elt, kv_elt;         // weight planes, activation planes, bytes per weight / per KV element
   TreeDev tree_h; TreeDev* tree_d;
   int M, D, Mmax, max_level_rows;
@@ -247,13 +251,19 @@ static int check_cfg(const eagle_config* c) {
   if (c->max_seq < c->n_nodes + 2) return fail(EAGLE_EINVAL, "max_seq too small for the tree");
   if (!(c->temperature >= 0.f)) return fail(EAGLE_EINVAL, "temperature must be >= 0");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(EAGLE_EINVAL, "bad rms_eps / rope_theta");
+  if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4) return fail(EAGLE_EINVAL, "weight_bits must be 0 / 16 (weights as given) or 4");
   return EAGLE_OK;
 }
 
-static void take_packed(Arena& a, PackedW& w, int N, int K, int NWP) {
+static void take_packed(Arena& a, PackedW& w, int N, int K, int NWP, bool q4 = false) {
   w.N = N; w.K = K; w.Npad = (N + 31) / 32 * 32; w.NRB = w.Npad / 32; w.KS = K / 16;
   w.plane_stride = (size_t)w.Npad * K;
-  w.w = a.take<bf16_t>(w.plane_stride * NWP);
+  w.q4 = q4;
+  if (q4) {
+    w.NG = K / EAGLE_Q4_GROUP;
+    w.w = a.take<bf16_t>(w.plane_stride / 4);                 // half a byte per weight
+    w.sc = a.take<bf16_t>((size_t)w.NRB * w.NG * 32);
+  } else w.w = a.take<bf16_t>(w.plane_stride * NWP);
 }
 
 // Lays the context's buffers out in the workspace (or just measures when c->ws == nullptr).
@@ -267,23 +277,23 @@ static size_t layout(eagle_ctx* c) {
   c->rope_sin = a.take<float>((size_t)g.max_seq * dh / 2);
   // weights
   c->embed = a.take<char>((size_t)V * d * c->elt);
-  take_packed(a, c->lm_head, V, d, c->NWP);
-  take_packed(a, c->fc, d, 2 * d, c->NWP);
+  take_packed(a, c->lm_head, V, d, c->NWP, c->q4);
+  take_packed(a, c->fc, d, 2 * d, c->NWP, c->q4);
   c->final_norm = a.take<float>(d);
   c->fc_bias = a.take<float>(d);
   c->layers.assign(g.n_layers + 1, LayerW());
   for (int l = 0; l <= g.n_layers; ++l) {
     LayerW& w = c->layers[l];
-    take_packed(a, w.qkv, (H + 2 * KVH) * dh, d, c->NWP);
-    take_packed(a, w.o, d, H * dh, c->NWP);
+    take_packed(a, w.qkv, (H + 2 * KVH) * dh, d, c->NWP, c->q4);
+    take_packed(a, w.o, d, H * dh, c->NWP, c->q4);
     w.moe = g.n_experts > 0 && (l < g.n_layers || g.draft_moe);
     if (w.moe) {
       w.e_gu.resize(g.n_experts); w.e_dn.resize(g.n_experts);
       for (int e = 0; e < g.n_experts; ++e) { take_packed(a, w.e_gu[e], 2 * F, d, c->NWP); take_packed(a, w.e_dn[e], d, F, c->NWP); }
       w.router = a.take<float>((size_t)g.n_experts * d);
     } else {
-      take_packed(a, w.gu, 2 * F, d, c->NWP);
-      take_packed(a, w.dn, d, F, c->NWP);
+      take_packed(a, w.gu, 2 * F, d, c->NWP, c->q4);
+      take_packed(a, w.dn, d, F, c->NWP, c->q4);
     }
     w.attn_norm = a.take<float>(d);
     w.mlp_norm = a.take<float>(d);
@@ -396,12 +406,21 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   c->f32 = cfg->dtype == EAGLE_F32;
   c->NWP = c->f32 ? 3 : 1; c->NXP = c->f32 ? 3 : 2; c->elt = c->f32 ? 4 : 2;
   c->kv_f32 = cfg->kv_dtype == EAGLE_F32; c->kv_elt = c->kv_f32 ? 4 : 2;
+  c->q4 = cfg->weight_bits == 4;
   c->M = c->tree_h.M; c->D = c->tree_h.D;
   c->max_level_rows = 1;
   for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
   if (cfg->max_batch * c->M > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
   // (the large-M GEMM walks K in stages of 4 k-steps: every K of the model must be a multiple of 64)
   c->pf_chunk = (!c->f32 && cfg->n_experts == 0 && cfg->d_ffn % 64 == 0 && (cfg->n_heads * cfg->head_dim) % 64 == 0) ? 512 : EAGLE_PREFILL_CHUNK;
+  if (c->q4) {
+    // 4-bit weights exist in the fused kernels of the fast path only: every pass has at most 32 rows, the prompt included
+    if (c->f32 || cfg->n_experts > 0) return fail(EAGLE_EINVAL, "weight_bits = 4 needs a dense bf16 model");
+    if (cfg->d_model % EAGLE_Q4_GROUP || cfg->d_ffn % EAGLE_Q4_GROUP || (cfg->n_heads * cfg->head_dim) % EAGLE_Q4_GROUP)
+      return fail(EAGLE_EINVAL, "weight_bits = 4 needs d_model, d_ffn and n_heads * head_dim to be multiples of %d", EAGLE_Q4_GROUP);
+    if (cfg->max_batch * c->M > 32 || cfg->max_batch * (c->D + 1) > 32) return fail(EAGLE_EINVAL, "weight_bits = 4: max_batch * n_nodes and max_batch * (depth + 1) must not exceed 32 rows");
+    c->pf_chunk = 32;
+  }
   int rows = std::max(c->pf_chunk, cfg->max_batch * c->M);
   c->Mmax = (rows + 31) / 32 * 32;
   return EAGLE_OK;
@@ -508,6 +527,12 @@ static int pack_into(eagle_ctx* c, const void* src, PackedW& w, int N, int K, in
   if (last > w.Npad) return fail(EAGLE_EINVAL, "internal: packed rows overflow");
   if (mode == PACK_ROPE && N % c->cfg.head_dim) return fail(EAGLE_EINVAL, "internal: rope packing needs whole heads");
   if ((mode == PACK_GATE || mode == PACK_UP) && N % 16) return fail(EAGLE_EINVAL, "d_ffn must be a multiple of 16");
+  if (w.q4) {
+    const size_t items = (size_t)(mode == PACK_PLAIN ? (N + 31) / 32 * 32 : N) * w.NG;
+    k_pack_weight_q4<bf16_t><<<(unsigned)((items + 255) / 256), 256, 0, c->stream>>>((const bf16_t*)src, (uint32_t*)w.w, w.sc, N, K, row_offset, mode, c->cfg.head_dim);
+    LAUNCH_CHECK();
+    return EAGLE_OK;
+  }
   size_t total = (size_t)((N + 31) / 32) * w.KS * 64;
   int blocks = (int)((total + 255) / 256);
   if (c->f32) k_pack_weight<float><<<blocks, 256, 0, c->stream>>>((const float*)src, w.w, N, K, row_offset, w.KS, c->NWP, w.plane_stride, mode, c->cfg.head_dim);
@@ -835,6 +860,19 @@ static hipError_t launch_fk(eagle_ctx* c, double bytes, const Gemm2& g, int grid
 }
 
 template <int NRMAX>
+static hipError_t launch_fk_q4(eagle_ctx* c, double bytes, const Gemm2& g, int grid) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)8 * NRMAX * 4096 + (g.epi == EPI_RESID ? (size_t)NRMAX * 32 * 33 * 4 : 0);
+  if (lds > 144 * 1024) return hipErrorInvalidValue;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_fk<1, 2, NRMAX, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  return launch_k(c, c->cur_class, bytes, "k2_gemm_fk<4-bit weights>", k2_gemm_fk<1, 2, NRMAX, false, true>, dim3(grid), dim3(V2_THREADS), lds, g);
+}
+
+template <int NRMAX>
 static hipError_t launch_xk(eagle_ctx* c, double bytes, const Gemm2& g) {
   static bool attr_set = false;
   const size_t lds = (size_t)8 * NRMAX * 4096;
@@ -859,8 +897,21 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   g.trace = (c->gemm_no++ == c->trace_sel && p.groups * p.S <= 1024) ? c->trace : nullptr;
   if (g.ssq_out && p.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
   if (groups_out) *groups_out = p.groups;
-  const double bytes = (double)w.N * w.K * c->elt;
+  const double bytes = w.bytes(c->elt);
   hipError_t e;
+  if (w.q4) {
+    // 4-bit weights: always the whole-K kernel (the weight stream is a quarter of the bf16 one: per-kernel fixed costs and
+    // the activation fragments dominate, an exchange of partial sums would cost more than idle CUs on narrow matrices)
+    const int grid = std::max(c->n_cu, (w.NRB + 1) / 2);      // at most two row blocks per work-group (three spill registers)
+    const int nrmax = (w.NRB + grid - 1) / grid;
+    if (g.epi == EPI_RESID && (grid > 256 || nrmax > 2)) return fail(EAGLE_EINVAL, "internal: residual epilogue on a matrix with %d row blocks", w.NRB);
+    g.SC = w.sc; g.NG = w.NG;
+    g.trace = nullptr;
+    if (groups_out) *groups_out = grid;
+    e = nrmax <= 1 ? launch_fk_q4<1>(c, bytes, g, grid) : launch_fk_q4<2>(c, bytes, g, grid);
+    if (e != hipSuccess) return fail(EAGLE_EHIP, "4-bit gemm launch failed: %s", hipGetErrorString(e));
+    return EAGLE_OK;
+  }
   // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials) ...
   const int fk_grid = std::max(c->n_cu, (w.NRB + 3) / 4);
   const bool fits_rsrc = (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
@@ -1002,7 +1053,8 @@ static int lm_head2(eagle_ctx* c, const Pass& pass, int M, bool scaled, float* o
   return (c->cur_class = KC_LMHEAD, gemm2(c, c->lm_head, c->xf2_d, g, nullptr));
 }
 
-static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, float* logits_out, int out_kind) {
+static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, float* logits_out, int out_kind,
+                           bool want_logits = true, int only_last_row = 0) {
   const eagle_config& cf = c->cfg;
   const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
   int rc;
@@ -1017,10 +1069,11 @@ static int target_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_ne
   LAUNCH_CHECK();
   k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->featbuf, c->F, c->pend_f, c->chunk_f, d);
   LAUNCH_CHECK();
-  return lm_head2(c, pass, M, true, logits_out, out_kind, 0);
+  if (!want_logits) return EAGLE_OK;
+  return lm_head2(c, pass, M, true, logits_out, out_kind, only_last_row);
 }
 
-static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, bool store_rows = true) {
+static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new, bool store_rows = true, bool want_logits = true) {
   const eagle_config& cf = c->cfg;
   const int M = pass.rows_per_seq * pass.n_seq, d = cf.d_model;
   int rc;
@@ -1032,6 +1085,7 @@ static int head_forward2(eagle_ctx* c, const Pass& pass, int ctx_max, int n_new,
   g.gain_next = c->layers[cf.n_layers].attn_norm; g.xf_out = c->xf2_d; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
   if ((rc = (c->cur_class = KC_FC, gemm2(c, c->fc, c->xf2_2d, g, &c->ssq2_groups)))) return rc;
   if ((rc = layer2(c, pass, M, cf.n_layers, ctx_max, n_new, nullptr))) return rc;
+  if (!want_logits) return EAGLE_OK;         // prompt rows of the head: only their cache entries are wanted
   if (store_rows) {                          // (the draft passes leave this copy to k_expand)
     k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->h2, c->node_f, c->pend_f, c->chunk_f, d);
     LAUNCH_CHECK();
@@ -1074,7 +1128,9 @@ extern "C" int eagle_prefill(eagle_ctx* c, int32_t seq, const int32_t* prompt, i
     const bool last = start + cn == n;
     c->last_chunk_rows = cn; c->last_chunk_start = start;
     Pass pt{PASS_PREFILL_T, cn, 1, seq, 0, start, cn};
-    if ((rc = target_forward(c, pt, start + cn, cn, last, c->vanilla_logits, 1, 1))) return rc;
+    const bool fast = cn <= 32 && c->q4;     // 4-bit weights: the prompt walks through the fused kernels 32 rows at a time
+    if ((rc = fast ? target_forward2(c, pt, start + cn, cn, c->vanilla_logits, 1, last, 1)
+                   : target_forward(c, pt, start + cn, cn, last, c->vanilla_logits, 1, 1))) return rc;
     if (last) {
       k_choose<<<1, 1024, 0, c->stream>>>(c->st, seq, c->vanilla_logits, g.vocab, g.temperature, g.seed, c->pbuf, 1, n, c->D);
       LAUNCH_CHECK();
@@ -1085,7 +1141,7 @@ extern "C" int eagle_prefill(eagle_ctx* c, int32_t seq, const int32_t* prompt, i
     const int dn = last ? cn - 1 : cn;
     if (dn > 0) {
       Pass pd{PASS_PREFILL_D, dn, 1, seq, 0, start, dn};
-      if ((rc = head_forward(c, pd, start + dn, dn, false))) return rc;
+      if ((rc = fast ? head_forward2(c, pd, start + dn, dn, false, false) : head_forward(c, pd, start + dn, dn, false))) return rc;
     }
   }
   int tok = 0;
@@ -1294,11 +1350,11 @@ extern "C" int eagle_step(eagle_ctx* c, int32_t* out_tokens, int32_t* out_len, i
     c->prof.draft_ms += a; c->prof.verify_ms += b; c->prof.accept_ms += d; c->prof.steps += 1;
     // algorithmic bytes of this verify: every target weight once, KV read of the context, KV write + logits
     const eagle_config& g = c->cfg;
-    double wbytes = (double)g.vocab * g.d_model * c->elt;
+    double wbytes = c->lm_head.bytes(c->elt);
     for (int l = 0; l < g.n_layers; ++l) {
       const LayerW& w = c->layers[l];
-      wbytes += ((double)w.qkv.N * w.qkv.K + (double)w.o.N * w.o.K) * c->elt;
-      if (!w.moe) wbytes += ((double)w.gu.N * w.gu.K + (double)w.dn.N * w.dn.K) * c->elt;
+      wbytes += w.qkv.bytes(c->elt) + w.o.bytes(c->elt);
+      if (!w.moe) wbytes += w.gu.bytes(c->elt) + w.dn.bytes(c->elt);
     }
     if (g.n_experts > 0) {   // experts that at least one row selected, summed over the layers (counted on the device)
       int touched = 0;

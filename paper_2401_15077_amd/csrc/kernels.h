@@ -196,6 +196,58 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
   }
 }
 
+// ---- 4-bit weights (Sec. 4.2: the int4 case study) ---------------------------------------------------------------------
+// Weight-only, symmetric, groups of 128 input columns: s = bf16(max|w| / 7), code = clip(rint(w / s), -8, 7) + 8, value
+// s * (code - 8).  Layout: "super-tiles" of 32 rows x 64 k = 1 KiB, tile (rb, T) at ((rb*KT + T) * 64) 16-byte lane
+// chunks (KT = K / 64); lane l (row l%32, k-half l/32) holds four 32-bit words, word j = the 8 codes of k-step j of
+// the super-tile, k = 64T + 16j + 8(l/32) + e, with code e at bit 4*(e/2) + 16*(e%2): ((word >> 4p) & 0x000F000F) |
+// 0x43004300 is then the bf16 pair (128 + code 2p, 128 + code 2p+1), i.e. the MFMA A operand of the k-step comes out of
+// one shift and one and-or per pair (128 + c is exact in bf16; the offset 136 = 128 + 8 is taken off per group).
+// Scales: bf16 [rb][group][lane-half][16] in accumulator-register order: entry (hh, r) belongs to row
+// 8*(r/4) + 4*hh + r%4 of the block, so a lane reads the scales of its 16 accumulator rows as 32 contiguous bytes.
+#define EAGLE_Q4_GROUP 128
+template <typename SrcT>
+__global__ __launch_bounds__(256) void k_pack_weight_q4(const SrcT* __restrict__ src, uint32_t* __restrict__ dst, bf16_t* __restrict__ sc,
+                                                        int N, int K, int row_offset, int mode, int dh) {
+  const int NG = K / EAGLE_Q4_GROUP, KT = K / 64;
+  const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int nrows = mode == PACK_PLAIN ? (N + 31) / 32 * 32 : N;          // only the plain map pads its last block
+  if (gid >= (size_t)nrows * NG) return;
+  const int n = (int)(gid / NG), g = (int)(gid % NG);
+  float w[EAGLE_Q4_GROUP];
+  float mx = 0.f;
+  for (int t = 0; t < EAGLE_Q4_GROUP; ++t) {
+    float x = 0.f;
+    if (n < N) {
+      if constexpr (sizeof(SrcT) == 4) x = ((const float*)src)[(size_t)n * K + g * EAGLE_Q4_GROUP + t];
+      else x = bf16_to_f32(((const bf16_t*)src)[(size_t)n * K + g * EAGLE_Q4_GROUP + t]);
+    }
+    w[t] = x;
+    mx = fmaxf(mx, fabsf(x));
+  }
+  const bf16_t sb = f32_to_bf16(mx / 7.0f);
+  const float s = bf16_to_f32(sb), safe = s > 0.f ? s : 1.0f;
+  const int prow = row_offset + pack_row_map(mode, n, dh);
+  const int rb = prow >> 5, rho = prow & 31, hh = (rho >> 2) & 1, r = 4 * (rho >> 3) + (rho & 3);
+  sc[(((size_t)rb * NG + g) * 2 + hh) * 16 + r] = sb;
+  for (int st = 0; st < 2; ++st) {                                        // the group's two super-tiles
+    const int T = 2 * g + st;
+    for (int kh = 0; kh < 2; ++kh) {
+      uint32_t words[4];
+      for (int j = 0; j < 4; ++j) {
+        uint32_t wd = 0;
+        for (int e = 0; e < 8; ++e) {
+          const float q = fminf(fmaxf(rintf(w[64 * st + 16 * j + 8 * kh + e] / safe), -8.f), 7.f);
+          wd |= (uint32_t)((int)q + 8) << (4 * (e >> 1) + 16 * (e & 1));
+        }
+        words[j] = wd;
+      }
+      u32x4 v; v.x = words[0]; v.y = words[1]; v.z = words[2]; v.w = words[3];
+      *(u32x4*)(dst + (((size_t)rb * KT + T) * 64 + rho + 32 * kh) * 4) = v;
+    }
+  }
+}
+
 // ============================================================================ skinny weight-streaming GEMM
 // PT[s][m][n] = sum over the split's k range of W[n][k] * X[m][k];  W packed (NWP bf16 planes), X in XF layout
 // (NXP bf16 planes, MT 32-row tiles).  A block is 4 waves; wave w owns row-block blockIdx.x*4+w (32 rows of W)

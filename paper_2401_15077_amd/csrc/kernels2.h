@@ -126,6 +126,7 @@ struct Gemm2 {
   const float* h_in; float* h_out; const float* bias; const float* gain_next; bf16_t* xf_out; int xf_KS; float* ssq_out; int d;
   // EPI_LOGITS
   float* logits; int out_kind, V, only_last_row;
+  const bf16_t* SC; int NG;               // 4-bit weights: scales [NRB][NG][2][16] and groups along K (W then holds codes)
   const float* row_w;                     // MoE: per-row routing weight applied to this GEMM's result (nullptr = 1)
   const int* skip_flag;                   // MoE: the whole launch is a no-op when *skip_flag == 0 (no row uses the expert)
   unsigned long long* trace;              // profiling builds (-DEAGLE_TRACE) only: [work-group][8] time stamps of this launch
@@ -664,6 +665,93 @@ __device__ __forceinline__ void fk_stream_dispatch(int nr, const bf16_t* XF, int
   else if constexpr (NR > 1) fk_stream_dispatch<NWP, NXP, NR - 1, WB>(nr, XF, KS, M, kb, ke, wp, wps, acc, lane, hw);
 }
 
+// ---- the same stream over 4-bit weights (see k_pack_weight_q4 for the layout) -------------------------------------------
+// A wave owns the groups [gb, ge) of 128 k.  Per group: two 16-byte loads per row block bring the codes of its 8 k-steps;
+// a k-step's A operand is 128 + code (exact in bf16) -- two ALU operations per pair of codes, which run beside the MFMAs
+// -- so the group's partial sums come out as sum_k x_k (128 + c_k); an MFMA against an all-ones tile gives sum_k x_k of
+// the same k-steps, and the group is folded into the result as  acc += s_row * (partial - 136 * sum_x)  in fp32.
+// Activation fragments are streamed from L2 as in fk_stream, one group (8 k-steps) ahead; the next group's codes are
+// requested as soon as a super-tile's registers are free.
+template <int NXP, int NR>
+__device__ __forceinline__ void fk_stream_q4(const bf16_t* __restrict__ XF, int KS, int M, int gb, int ge, const u32x4* const* wq,
+                                             const u32x4* const* sq /*scales of (block j, group 0), this lane's half*/, int NG,
+                                             f32x16* acc, int lane) {
+  if (ge <= gb) return;
+  const int glast = ge - 1;
+  const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)XF, 0, NXP * KS * 1024, 0x00020000);
+  const uint32_t xlane = (lane & 31) < M ? (uint32_t)lane * 16u : 0x80000000u;   // dead rows: out of range -> zeros
+#define Q4_XLOAD(q, kk) __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, (uint32_t)(((q) * KS + (kk)) * 1024), 0))
+  u32x4 a4[2][NR], tb[8][NXP];                                 // codes of a group; activation fragments one group ahead
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int j = 0; j < NR; ++j) a4[st][j] = wq[j][(size_t)(2 * gb + st) * 64];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int q = 0; q < NXP; ++q) tb[i][q] = Q4_XLOAD(q, 8 * gb + i);
+  for (int g = gb; g < ge; ++g) {
+    f32x16 part[NR], sx;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sx[r] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NR; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[j][r] = 0.f;
+    u32x4 sraw[NR][2];                                          // this group's scales: needed after its 8 k-steps
+#pragma unroll
+    for (int j = 0; j < NR; ++j) { sraw[j][0] = sq[j][(size_t)g * 4]; sraw[j][1] = sq[j][(size_t)g * 4 + 1]; }
+    const int gn = min(g + 1, glast);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int kk = 8 * g + 4 * st + ks;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+          const uint32_t wd = ks == 0 ? a4[st][j].x : ks == 1 ? a4[st][j].y : ks == 2 ? a4[st][j].z : a4[st][j].w;
+          u32x4 av;
+          av.x = (wd & 0x000F000Fu) | 0x43004300u;
+          av.y = ((wd >> 4) & 0x000F000Fu) | 0x43004300u;
+          av.z = ((wd >> 8) & 0x000F000Fu) | 0x43004300u;
+          av.w = ((wd >> 12) & 0x000F000Fu) | 0x43004300u;
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), part[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NXP; ++q)
+          sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), sx, 0, 0, 0);
+        // use a slot, refill that slot: the same k-step of the next group
+        (void)kk;
+#pragma unroll
+        for (int q = 0; q < NXP; ++q) tb[4 * st + ks][q] = Q4_XLOAD(q, 8 * gn + 4 * st + ks);
+      }
+      // the super-tile's code registers are free: request the next group's
+#pragma unroll
+      for (int j = 0; j < NR; ++j) a4[st][j] = wq[j][(size_t)(2 * gn + st) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+      const uint32_t sw[8] = {sraw[j][0].x, sraw[j][0].y, sraw[j][0].z, sraw[j][0].w, sraw[j][1].x, sraw[j][1].y, sraw[j][1].z, sraw[j][1].w};
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float sv = __builtin_bit_cast(float, (r & 1) ? (sw[r >> 1] & 0xFFFF0000u) : (sw[r >> 1] << 16));
+        acc[j][r] += sv * (part[j][r] - 136.0f * sx[r]);
+      }
+    }
+  }
+#undef Q4_XLOAD
+}
+template <int NXP, int NR>
+__device__ __forceinline__ void fk_stream_q4_dispatch(int nr, const bf16_t* XF, int KS, int M, int gb, int ge, const u32x4* const* wq,
+                                                      const u32x4* const* sq, int NG, f32x16* acc, int lane) {
+  if (nr == NR) fk_stream_q4<NXP, NR>(XF, KS, M, gb, ge, wq, sq, NG, acc, lane);
+  else if constexpr (NR > 1) fk_stream_q4_dispatch<NXP, NR - 1>(nr, XF, KS, M, gb, ge, wq, sq, NG, acc, lane);
+}
+
 // sum over the 8 waves of element (row n_local of row block j, token m) of the per-wave accumulators parked in LDS
 // as red[w][j][r][lane] (MFMA layout: r = 4*(n_local/8) + n_local%4, lane = m + 32*((n_local/4)%2)); k-part order
 __device__ inline float fk_sum(const float* red, int nrmax, int j, int n_local, int m) {
@@ -680,8 +768,9 @@ __device__ inline float fk_sum(const float* red, int nrmax, int j, int n_local, 
 // keeps them whole-K: no partial sums are exchanged).  A work-group then owns a run of halves; of a block it shares
 // with a neighbour it loads and finishes only its own 16 rows (the other lanes of the tile load nothing and multiply
 // zeros).  Rotate-half pairs are adjacent rows, so a half holds whole pairs.  Epilogues: QKV and the residual one.
-template <int NWP, int NXP, int NRMAX, bool HALF = false>
+template <int NWP, int NXP, int NRMAX, bool HALF = false, bool Q4 = false>
 __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
+  static_assert(!Q4 || (!HALF && NWP == 1), "4-bit weights: whole row blocks, one plane");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sh_small[16 * 33];
   __shared__ float rstd_s[32];
@@ -736,6 +825,19 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
       }
     }
   }
+  if constexpr (Q4) {
+    // K is split over the waves by groups of 128; pointers to the codes / scales of each row block
+    const int gb = (unsigned)w * (unsigned)g.NG / 8u, ge = (unsigned)(w + 1) * (unsigned)g.NG / 8u;
+    const u32x4* wq[NRMAX];
+    const u32x4* sq[NRMAX];
+#pragma unroll
+    for (int j = 0; j < NRMAX; ++j) {
+      const size_t rb = (size_t)min(rb0 + j, g.NRB - 1);
+      wq[j] = (const u32x4*)g.W + rb * (size_t)(g.KS / 4) * 64 + lane;
+      sq[j] = (const u32x4*)g.SC + rb * (size_t)g.NG * 4 + 2 * (lane >> 5);
+    }
+    fk_stream_q4_dispatch<NXP, NRMAX>(nr, g.XF, g.KS, g.M, gb, ge, wq, sq, g.NG, acc, lane);
+  } else
   fk_stream_dispatch<NWP, NXP, NRMAX, HALF>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane, &hw);
   TRACE_STAMP_AFTER(tr, 2, acc[0][0]);
   // park every wave's sums in LDS
