@@ -82,6 +82,7 @@ struct eagle_ctx {
   hipStream_t stream;
   char* ws; size_t ws_bytes;
   bool f32, kv_f32, q4 = false;      // q4: weight matrices stored in 4 bits (fast path only)
+  bool q4_staged = true;
   int NWP, NXP, elt, kv_elt;         // weight planes, activation planes, bytes per weight / per KV element
   TreeDev tree_h; TreeDev* tree_d;
   int M, D, Mmax, max_level_rows;
@@ -173,18 +174,20 @@ static PlanXK plan_xk(int NRB, int KS, int NXP, int n_cu, size_t pt_floats_per_s
 // Work split of the LDS-staged split-K kernel: S K-slices x `groups` row groups = one work-group each; inside a
 // work-group `lanes` x `kparts` waves (product 8): a wave owns every lanes-th row block of the group over one k-part.
 struct Plan2 { int S, groups, lanes, kparts, RW, kt_max; size_t lds; };
-static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu) {
+static Plan2 plan2(int NRB, int KS, int NXP, int NWP, int n_cu, bool q4 = false) {
   Plan2 p;
   const int x_cap_kb = 128;                                   // LDS given to the X slice / the wave reduction
   int S = 1;
-  while ((NXP * ((KS + S - 1) / S)) > x_cap_kb) ++S;          // fewest K slices whose X slice fits (fewer partials to exchange)
+  // fewest K slices whose X slice fits (fewer partials to exchange); 4-bit weights: slices are whole groups of 8 k-steps
+  auto slice_ks = [&](int S_) { return q4 ? 8 * ((KS / 8 + S_ - 1) / S_) : (KS + S_ - 1) / S_; };
+  while (NXP * slice_ks(S) > x_cap_kb) ++S;
   int groups = std::max(1, std::min(NRB, n_cu / S));
   // few row blocks: split K further (slices of at least 4 k-steps) until the grid fills the chip
-  while (groups * S * 2 <= n_cu && (KS + 2 * S - 1) / (2 * S) >= 4) S *= 2;
+  while (!q4 && groups * S * 2 <= n_cu && (KS + 2 * S - 1) / (2 * S) >= 4) S *= 2;
   // many row blocks (wide matrices with a long K): more work-groups than CUs rather than more than 3 row blocks per wave
   const int r_cap = 24;
   if ((NRB + groups - 1) / groups > r_cap) groups = (NRB + r_cap - 1) / r_cap;
-  const int R = (NRB + groups - 1) / groups, kt = (KS + S - 1) / S;
+  const int R = (NRB + groups - 1) / groups, kt = slice_ks(S);
   long best = -1; int bl = 8, bk = 1;
   const int cand[4][2] = {{8, 1}, {4, 2}, {2, 4}, {1, 8}};
   for (auto& cd : cand) {
@@ -370,7 +373,7 @@ static size_t layout(eagle_ctx* c) {
   c->cnt_gemm = a.take<int>(1024); c->cnt_attn = a.take<int>((size_t)128 * H);
   size_t worst2 = 0;
   auto consider2 = [&](const PackedW& w) {
-    Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
+    Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu, w.q4);
     worst2 = std::max(worst2, (size_t)p.S * w.Npad * 32);
   };
   consider2(c->lm_head); consider2(c->fc);
@@ -503,6 +506,7 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
     if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return fail(EAGLE_EHIP, "event creation failed"); }
   memset(&c->prof, 0, sizeof(c->prof));
 #ifdef EAGLE_TRACE
+  if (const char* t = getenv("EAGLE_Q4_STAGED")) c->q4_staged = atoi(t) != 0;
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   if (getenv("EAGLE_EXPAND_TRACE")) c->expand_trace = 1;
@@ -834,15 +838,15 @@ static int head_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, bo
 }
 
 // ---------------------------------------------------------------------------- fast path (<= 32 rows)
-template <int NWP, int NXP, int RW, int DEPTH>
+template <int NWP, int NXP, int RW, int DEPTH, bool Q4 = false>
 static hipError_t launch_k2(eagle_ctx* c, double bytes, const Gemm2& g, size_t lds) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm<NWP, NXP, RW, DEPTH>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm<NWP, NXP, RW, DEPTH, Q4>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  return launch_k(c, c->cur_class, bytes, "k2_gemm", k2_gemm<NWP, NXP, RW, DEPTH>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
+  return launch_k(c, c->cur_class, bytes, Q4 ? "k2_gemm<4-bit weights>" : "k2_gemm", k2_gemm<NWP, NXP, RW, DEPTH, Q4>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
 }
 
 template <int NRMAX, bool HALF = false>
@@ -886,7 +890,7 @@ static hipError_t launch_xk(eagle_ctx* c, double bytes, const Gemm2& g) {
 
 // Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
 static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int* groups_out) {
-  Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu);
+  Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu, w.q4);
   const int R = (w.NRB + p.groups - 1) / p.groups;
   if ((R + p.lanes - 1) / p.lanes > p.RW) return fail(EAGLE_EINVAL, "internal: %d row blocks per wave exceed the kernel's %d", (R + p.lanes - 1) / p.lanes, p.RW);
   if ((size_t)p.S * w.Npad * 32 > c->pt2_floats) return fail(EAGLE_EINVAL, "internal: fast-path partial buffer too small");
@@ -899,16 +903,30 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   if (groups_out) *groups_out = p.groups;
   const double bytes = w.bytes(c->elt);
   hipError_t e;
+  if (w.q4 && c->q4_staged && (g.epi == EPI_RESID || (w.NRB + 2) / 3 > c->n_cu)) {   // (or too many row blocks for one round of whole-K work-groups: the LM head)
+    // 4-bit weights, narrow matrices (O, down, FC): split-K with the activation slice staged in LDS.  With a quarter of
+    // the weight bytes the activation fragments are most of what a CU fetches; staged, a work-group fetches its K slice of
+    // them once.  (Measured at d = 4096: O 13.9 us against 15.0 whole-K, down 25.5 against 29.8, FC 18.9 against 21.8;
+    // the wide matrices are faster whole-K: QKV 20.2 against 27.3 -- their epilogues would run on 64 CUs only.)
+    g.SC = w.sc; g.NG = w.NG;
+    g.trace = nullptr;
+    switch (p.RW) {
+      case 1: e = launch_k2<1, 2, 1, 1, true>(c, bytes, g, p.lds); break;
+      case 2: e = launch_k2<1, 2, 2, 1, true>(c, bytes, g, p.lds); break;
+      default: e = launch_k2<1, 2, 3, 1, true>(c, bytes, g, p.lds); break;
+    }
+    if (e != hipSuccess) return fail(EAGLE_EHIP, "4-bit gemm launch failed: %s", hipGetErrorString(e));
+    return EAGLE_OK;
+  }
   if (w.q4) {
-    // 4-bit weights: always the whole-K kernel (the weight stream is a quarter of the bf16 one: per-kernel fixed costs and
-    // the activation fragments dominate, an exchange of partial sums would cost more than idle CUs on narrow matrices)
-    const int grid = std::max(c->n_cu, (w.NRB + 1) / 2);      // at most two row blocks per work-group (three spill registers)
+    // wide matrices: whole-K work-groups of up to three row blocks, epilogue in place
+    const int grid = std::max(c->n_cu, (w.NRB + 2) / 3);
     const int nrmax = (w.NRB + grid - 1) / grid;
     if (g.epi == EPI_RESID && (grid > 256 || nrmax > 2)) return fail(EAGLE_EINVAL, "internal: residual epilogue on a matrix with %d row blocks", w.NRB);
     g.SC = w.sc; g.NG = w.NG;
     g.trace = nullptr;
     if (groups_out) *groups_out = grid;
-    e = nrmax <= 1 ? launch_fk_q4<1>(c, bytes, g, grid) : launch_fk_q4<2>(c, bytes, g, grid);
+    e = nrmax <= 1 ? launch_fk_q4<1>(c, bytes, g, grid) : nrmax == 2 ? launch_fk_q4<2>(c, bytes, g, grid) : launch_fk_q4<3>(c, bytes, g, grid);
     if (e != hipSuccess) return fail(EAGLE_EHIP, "4-bit gemm launch failed: %s", hipGetErrorString(e));
     return EAGLE_OK;
   }

@@ -427,6 +427,79 @@ __device__ __forceinline__ void k2_stream(const u32x4* __restrict__ xs, int kt, 
   }
 }
 
+// ---- 4-bit weights against an activation slice in LDS (layout and arithmetic: see k_pack_weight_q4 / fk_stream_q4) ------
+// A wave owns NR row blocks over the groups [gb, ge) of the work-group's K slice (slice-relative group indices; the
+// slice starts at group g0 of the matrix).  With a quarter of the weight bytes the activation fragments are what a CU
+// fetches most of, so here they are fetched ONCE per work-group (into LDS) and every wave reads them from there.
+template <int NXP, int NR>
+__device__ __forceinline__ void k2_stream_q4(const u32x4* __restrict__ xs, int kt, int g0, int gb, int ge, const u32x4* const* wq,
+                                             const u32x4* const* sq, f32x16* acc, int lane) {
+  if (ge <= gb) return;
+  const int glast = ge - 1;
+  u32x4 a4[2][NR];
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int j = 0; j < NR; ++j) a4[st][j] = wq[j][(size_t)(2 * (g0 + gb) + st) * 64];
+  for (int g = gb; g < ge; ++g) {
+    f32x16 part[NR], sx;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sx[r] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NR; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[j][r] = 0.f;
+    u32x4 sraw[NR][2];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) { sraw[j][0] = sq[j][(size_t)(g0 + g) * 4]; sraw[j][1] = sq[j][(size_t)(g0 + g) * 4 + 1]; }
+    const int gn = min(g + 1, glast);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int kk = 8 * g + 4 * st + ks;                    // k-step inside the slice
+        u32x4 bq[NXP];
+#pragma unroll
+        for (int q = 0; q < NXP; ++q) bq[q] = xs[((size_t)q * kt + kk) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+          const uint32_t wd = ks == 0 ? a4[st][j].x : ks == 1 ? a4[st][j].y : ks == 2 ? a4[st][j].z : a4[st][j].w;
+          u32x4 av;
+          av.x = (wd & 0x000F000Fu) | 0x43004300u;
+          av.y = ((wd >> 4) & 0x000F000Fu) | 0x43004300u;
+          av.z = ((wd >> 8) & 0x000F000Fu) | 0x43004300u;
+          av.w = ((wd >> 12) & 0x000F000Fu) | 0x43004300u;
+#pragma unroll
+          for (int q = 0; q < NXP; ++q)
+            part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bq[q]), part[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NXP; ++q)
+          sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, bq[q]), sx, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < NR; ++j) a4[st][j] = wq[j][(size_t)(2 * (g0 + gn) + st) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+      const uint32_t sw[8] = {sraw[j][0].x, sraw[j][0].y, sraw[j][0].z, sraw[j][0].w, sraw[j][1].x, sraw[j][1].y, sraw[j][1].z, sraw[j][1].w};
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float sv = __builtin_bit_cast(float, (r & 1) ? (sw[r >> 1] & 0xFFFF0000u) : (sw[r >> 1] << 16));
+        acc[j][r] += sv * (part[j][r] - 136.0f * sx[r]);
+      }
+    }
+  }
+}
+template <int NXP, int RW, int NR>
+__device__ __forceinline__ void k2_stream_q4_dispatch(int nr, const u32x4* xs, int kt, int g0, int gb, int ge, const u32x4* const* wq,
+                                                      const u32x4* const* sq, f32x16* acc, int lane) {
+  if (nr == NR) k2_stream_q4<NXP, NR>(xs, kt, g0, gb, ge, wq, sq, acc, lane);
+  else if constexpr (NR > 1) k2_stream_q4_dispatch<NXP, RW, NR - 1>(nr, xs, kt, g0, gb, ge, wq, sq, acc, lane);
+}
+
 template <int NWP, int NXP, int RW, int NR, int DEPTH>
 __device__ __forceinline__ void k2_prologue_dispatch(int nr, int kb, int ke, const u32x4* const* wp, size_t wps, u32x4* pre) {
   if (nr == NR) k2_prologue<NWP, NR, (DEPTH * RW) / NR>(kb, ke, wp, wps, pre);
@@ -439,7 +512,7 @@ __device__ __forceinline__ void k2_stream_dispatch(int nr, const u32x4* xs, int 
   else if constexpr (NR > 1) k2_stream_dispatch<NWP, NXP, RW, NR - 1, DEPTH>(nr, xs, kt, kb, ke, wp, wps, acc, lane, pre);
 }
 
-template <int NWP, int NXP, int RW, int DEPTH>
+template <int NWP, int NXP, int RW, int DEPTH, bool Q4 = false>
 __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sh_small[16 * 33];
@@ -451,9 +524,12 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   const unsigned uS = g.S, ugroups = g.groups, uNRB = g.NRB, uKS = g.KS, ulanes = g.lanes, ukparts = g.kparts;
   const int s = blockIdx.x % uS, grp = blockIdx.x / uS;
   const int rb0 = (unsigned)grp * uNRB / ugroups, rb1 = (unsigned)(grp + 1) * uNRB / ugroups;
-  const int ks0 = (unsigned)s * uKS / uS, ks1 = (unsigned)(s + 1) * uKS / uS, kt = ks1 - ks0;
+  // K slice of the work-group and K part of the wave: in k-steps, or (4-bit weights) in whole groups of 8 k-steps
+  const int gs0 = Q4 ? (int)((unsigned)s * (unsigned)g.NG / uS) : 0, gs1 = Q4 ? (int)((unsigned)(s + 1) * (unsigned)g.NG / uS) : 0;
+  const int ks0 = Q4 ? 8 * gs0 : (int)((unsigned)s * uKS / uS), ks1 = Q4 ? 8 * gs1 : (int)((unsigned)(s + 1) * uKS / uS), kt = ks1 - ks0;
   const int la = (unsigned)w % ulanes, kb_i = (unsigned)w / ulanes;
-  const int kb = (unsigned)kb_i * (unsigned)kt / ukparts, ke = (unsigned)(kb_i + 1) * (unsigned)kt / ukparts;
+  const int qgb = (unsigned)kb_i * (unsigned)(gs1 - gs0) / ukparts, qge = (unsigned)(kb_i + 1) * (unsigned)(gs1 - gs0) / ukparts;
+  const int kb = Q4 ? 8 * qgb : (int)((unsigned)kb_i * (unsigned)kt / ukparts), ke = Q4 ? 8 * qge : (int)((unsigned)(kb_i + 1) * (unsigned)kt / ukparts);
   unsigned long long* tr = TRACE_PTR((g.trace && threadIdx.x == 0) ? g.trace + (size_t)blockIdx.x * 8 : nullptr);
   TRACE_STAMP(tr, 0);
   int nr = 0;
@@ -469,7 +545,7 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
   }
   // the first weight tiles are requested before anything else (a wave with fewer row blocks keeps more k-steps in flight)
   u32x4 pre[DEPTH * RW * NWP];
-  k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
+  if constexpr (!Q4) k2_prologue_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, kb, ke, wp, g.wps, pre);
 
   // row facts and the 1/rms inputs the epilogue will want: requested now, used (by the last work-group) much later
   RowPre rp;
@@ -515,6 +591,18 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm(Gemm2 g) {
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   __syncthreads();
   TRACE_STAMP(tr, 1);
+  if constexpr (Q4) {
+    const u32x4* wq[RW];
+    const u32x4* sq[RW];
+#pragma unroll
+    for (int j = 0; j < RW; ++j) {
+      int rb = rb0 + la + j * g.lanes;
+      if (rb >= rb1) rb = rb0;
+      wq[j] = (const u32x4*)g.W + (size_t)rb * (size_t)(g.KS / 4) * 64 + lane;
+      sq[j] = (const u32x4*)g.SC + (size_t)rb * (size_t)g.NG * 4 + 2 * (lane >> 5);
+    }
+    k2_stream_q4_dispatch<NXP, RW, RW>(nr, xs, kt, gs0, qgb, qge, wq, sq, acc, lane);
+  } else
   k2_stream_dispatch<NWP, NXP, RW, RW, DEPTH>(nr, xs, kt, kb, ke, wp, g.wps, acc, lane, pre);
   TRACE_STAMP(tr, 2);
   // waves that split K inside the work-group: sum through LDS in k-part order
