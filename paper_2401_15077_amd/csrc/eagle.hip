@@ -141,13 +141,18 @@ static GemmPlan plan_gemm(int NRB, int KS, int NXP, int MT) {
   return p;
 }
 
+// Which passes of the general path take the large-M GEMM: every pass of more than 128 rows (only prompts, and only
+// where the kernel exists), and batched tree passes of 65..128 rows of the models it covers.
+static bool use_pf(const eagle_ctx* c, int MT) { return MT > 4 || (MT >= 3 && c->pf_chunk == 512); }
+
 // Work split of the large-M GEMM (k_gemm_pf): work-group tiles of 8 row blocks x 4 row tiles; K is split only when the
 // tiles alone would leave most CUs idle (narrow matrices: O, down), since every split writes and re-reads M x N floats.
 static GemmPlan plan_pf(int NRB, int KS, int MT, int n_cu) {
   GemmPlan p;
   const int wgs = ((NRB + 7) / 8) * ((MT + 3) / 4);
-  int S = wgs * 2 > n_cu ? 1 : std::min(4, n_cu / std::max(1, wgs));
-  S = std::max(1, std::min(S, KS / 32));
+  // one tile of rows (a batched tree pass): the weights are streamed once, so deeper splits pay for themselves
+  int S = wgs * 2 > n_cu ? 1 : std::min(MT <= 4 ? 16 : 4, n_cu / std::max(1, wgs));
+  S = std::max(1, std::min(S, KS / (MT <= 4 ? 16 : 32)));
   p.ks_per_split = ((KS + S - 1) / S + 3) / 4 * 4;
   p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
   p.chunk = 4;
@@ -344,7 +349,7 @@ static size_t layout(eagle_ctx* c) {
   size_t worst = 0;
   auto consider = [&](const PackedW& w) {
     for (int mt = 1; mt <= MTm; ++mt) {
-      GemmPlan p = mt > 4 ? plan_pf(w.NRB, w.KS, mt, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, mt);
+      GemmPlan p = use_pf(c, mt) ? plan_pf(w.NRB, w.KS, mt, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, mt);
       worst = std::max(worst, (size_t)p.S * w.Npad * (size_t)(mt * 32));
     }
   };
@@ -650,7 +655,7 @@ static hipError_t launch_gemm_mt(eagle_ctx* c, const PackedW& w, const bf16_t* X
 
 // PT <- X (XF layout, MT row tiles) times W^T.  Returns the split count through *S.
 static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S) {
-  const bool big = MT > 4;
+  const bool big = use_pf(c, MT);
   GemmPlan p = big ? plan_pf(w.NRB, w.KS, MT, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, MT);
   if ((size_t)p.S * w.Npad * MT * 32 > c->pt_floats) return fail(EAGLE_EINVAL, "internal: partial buffer too small");
   if (MT < 1 || MT * 32 > c->Mmax || (big && c->f32)) return fail(EAGLE_EINVAL, "internal: MT out of range");
