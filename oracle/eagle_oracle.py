@@ -33,9 +33,14 @@ Readings where the paper is silent or garbled (listed in full in the design note
     kv_store="bf16" every K/V row is rounded to bf16 (nearest-even) when it is written to the cache --
     a storage code both sides must produce identically -- and read back as that value
 
-PARITY UNPINNED (no value in the paper to compare with): the logits / features of the random-init
-models, and the default tree shapes (the paper's tree figure is not available in text form).
-Everything else is pinned by tests/test_oracle_*.py against closed forms, enumeration and invariants.
+  * inverse-CDF draws carry the running sum in float64 whatever `dtype` is (a float32 running sum over
+    a LLaMA-sized vocabulary is uncertain by more than many bins are wide)
+
+PARITY UNPINNED (no value in the paper to compare with): the default tree shapes (the paper's tree
+figure is not available in text form).  The layer arithmetic (attention scale, GQA map, tree mask,
+RoPE, SwiGLU, MoE routing), the head over a tree, the stochastic tree builder and the acceptance rules
+are pinned by tests/test_oracle_pins.py and tests/test_oracle_pins_layer.py against worked examples,
+closed forms, enumeration and invariants, each with a planted mistake shown to fail.
 """
 from __future__ import annotations
 

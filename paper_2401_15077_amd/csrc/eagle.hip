@@ -796,9 +796,10 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   return resnorm(c, M, MT, c->h, c->PT, S, w.dn.Npad, nullptr, next_gain, c->xf_d, xout);
 }
 
-static int lm_head(eagle_ctx* c, const Pass& pass, int M, int MT, float* out, int out_kind, int only_last_row) {
+static int lm_head(eagle_ctx* c, const Pass& pass, int M, int MT, float* out, int out_kind, int only_last_row,
+                   const bf16_t* XF = nullptr) {
   int S, rc;
-  if ((rc = (c->cur_class = KC_LMHEAD, gemm(c, c->lm_head, c->xf_d, MT, &S)))) return rc;
+  if ((rc = (c->cur_class = KC_LMHEAD, gemm(c, c->lm_head, XF ? XF : c->xf_d, MT, &S)))) return rc;
   dim3 grid((c->cfg.vocab + 255) / 256, M);
   k_logits<<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, c->lm_head.Npad, MT * 32, out, out_kind, c->cfg.vocab, only_last_row);
   LAUNCH_CHECK();
@@ -820,6 +821,15 @@ static int target_forward(eagle_ctx* c, const Pass& pass, int t_max, int n_new, 
   }
   k_store_rows<<<M, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->featbuf, c->F, c->pend_f, c->chunk_f, g.d_model);
   LAUNCH_CHECK();
+  if (want_logits && only_last_row && pass.kind == PASS_PREFILL_T && MT > 1) {
+    // a prompt pass needs the distribution of its last position only: the LM head runs over the last 32-row tile,
+    // whose features (already normalised) are re-laid as a one-tile GEMM input
+    const int row0 = (MT - 1) * 32, nr = M - row0;
+    if ((rc = resnorm(c, nr, 1, c->featbuf + (size_t)row0 * g.d_model, nullptr, 0, 0, nullptr, nullptr, c->xf_2d, nullptr))) return rc;
+    Pass sub = pass;
+    sub.rows_per_seq = nr; sub.chunk_start = pass.chunk_start + row0; sub.chunk_n = nr;
+    return lm_head(c, sub, nr, 1, logits_out, out_kind, only_last_row, c->xf_2d);
+  }
   if (want_logits) return lm_head(c, pass, M, MT, logits_out, out_kind, only_last_row);
   return EAGLE_OK;
 }
@@ -938,7 +948,10 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   // wide matrices of the bf16 configuration: whole-K work-groups with the epilogue in place (no partials) ...
   const int fk_grid = std::max(c->n_cu, (w.NRB + 3) / 4);
   const bool fits_rsrc = (size_t)w.NRB * w.KS * 1024 < ((size_t)1 << 31);
-  const bool fullk = !c->f32 && w.NRB >= c->n_cu && (g.epi != EPI_RESID || (fk_grid <= 256 && (w.NRB + fk_grid - 1) / fk_grid <= 2));
+  // (not for the residual epilogue, although the kernel has it: O and down at d = 8192 have exactly one row block per
+  // CU, and a work-group that owns one row block over all of K fetches twice as many activation bytes as weight
+  // bytes -- measured there: down 109.7 us whole-K against 85.8 us split-K, O 37.5 against 34.8)
+  const bool fullk = !c->f32 && w.NRB >= c->n_cu && g.epi != EPI_RESID;
   // ... and narrower ones with at least one HALF row block per CU (O, down, FC at d = 4096 / 5120): still whole-K, a
   // work-group owns one or two halves
   // (measured at d = 4096: 35.6 us against 26.0 for down, 16.0 against 14.2 for O -- every tile load of a work-group
