@@ -39,6 +39,40 @@ def solve_alpha(tau: float, D: int) -> float:
     return 0.5 * (lo + hi)
 
 
+def bench_head_loss(args, shape, torch, synth, pkg) -> int:
+    """Forward + gradient of the head's training loss on R rows (only the LM head of the shape is loaded).  A step is
+    one call: 2R rows through the LM head, the row-wise loss, R rows through its transpose.  Bound: the bf16 MFMA
+    rate (6 R V d algorithmic flop; the kernels multiply two bf16 planes per activation, i.e. twice that)."""
+    R, K, W = args.head_loss_rows, args.steps, args.warmup
+    par, rk = synth.TREES["T8"]
+    eng = pkg.Eagle(shape.twin(1), par, rk, max_batch=1, max_seq=128, head_loss_rows=R)
+    spec = [t for t in synth.tensor_specs(shape) if t[0] == "lm_head"][0]
+    eng.load_named("lm_head", synth.gen_tensor(shape, args.seed, spec, synth.device_fmt(shape)))
+    g = torch.Generator(device="cpu").manual_seed(args.seed)
+    f = torch.randn(R, shape.d_model, generator=g).cuda()
+    fhat = (f.cpu() + 0.6 * torch.randn(R, shape.d_model, generator=g)).cuda()
+    grad = torch.empty_like(f)
+    for _ in range(W):
+        eng.head_loss_device(f, fhat, grad)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        loss = eng.head_loss_device(f, fhat, grad)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flop = 6.0 * R * shape.vocab * shape.d_model
+    out = {"metric": "head training loss (forward + gradient), rows/s", "value": R * K / dt, "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{shape.name} LM head ({shape.vocab} x {shape.d_model}), {R} rows of N(0,1) features, prediction = label + 0.6 N(0,1), w_cls 0.1"},
+           "loss": {"L": loss[0], "L_reg": loss[1], "L_cls": loss[2]},
+           "roofline": {"bound": "mfma", "achieved": flop / (dt / K) / 1e12, "peak": 2500.0, "unit": "TFLOP/s", "frac": flop / (dt / K) / 2.5e15,
+                        "traffic": None, "note": "algorithmic flop 6 R V d over the whole call (its GEMMs, the row-wise loss kernel and the partial-sum pass)"},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+    eng.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +92,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=3)
     ap.add_argument("--cpu-prompt", type=int, default=48)
+    ap.add_argument("--head-loss-rows", type=int, default=0, help="> 0: time the head's training loss instead (Sec. 3.2: Smooth L1 + w_cls x cross entropy over the "
+                    "LM head, forward and gradient) on this many rows of synthetic features; prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no cross-GPU exchange); use --gpus 1", file=sys.stderr)
@@ -70,6 +106,8 @@ def main() -> int:
     shape = synth.SHAPES[args.shape]
     if args.layers:
         shape = shape.twin(args.layers)
+    if args.head_loss_rows > 0:
+        return bench_head_loss(args, shape, torch, synth, pkg)
     par, rk = synth.TREES[args.tree]
     K, W = args.steps, args.warmup
     M = len(par)

@@ -61,6 +61,12 @@ typedef struct {
                                          code = clip(rint(w / scale), -8, 7), value scale * code.  Needs a dense bf16
                                          model whose widths are multiples of 128, and at most 32 rows per pass
                                          (max_batch * n_nodes <= 32); the prompt then runs 32 rows at a time. */
+  int32_t head_loss_rows;             /* 0: off.  > 0: the workspace also holds what eagle_head_loss needs -- a second
+                                         copy of the LM head re-tiled for the product with its transpose, and one
+                                         pass's gradient of the logits -- (about 2 * vocab * d_model + 4 * vocab * pass
+                                         rows bytes); needs a bf16 model with weight_bits 0 / 16 and vocab % 64 == 0.
+                                         The value itself only switches the feature on: any row count is processed in
+                                         passes. */
 } eagle_config;
 
 /* Which tensor eagle_load_weight() is given.  Matrices are row-major [out_features, in_features] in the
@@ -209,6 +215,28 @@ int eagle_get_profile(eagle_ctx *ctx, eagle_profile *out, int32_t reset);
  * that ran.  Up to `cap` entries are written, *n of them. */
 typedef struct { char name[16]; char kernel[48]; double ms; int64_t launches; double bytes; } eagle_kernel_stat;
 int eagle_get_kernel_stats(eagle_ctx *ctx, int32_t phase, eagle_kernel_stat *out, int32_t cap, int32_t *n, int32_t reset);
+
+/* Training loss of the Autoregression Head and its gradient (Sec. 3.2 "Training of the draft models"):
+ *   L_reg = mean over rows and columns of SmoothL1(fhat - f)      (threshold 1: 0.5 x^2 if |x| < 1, else |x| - 0.5)
+ *   L_cls = mean over rows of -sum_v p_v log phat_v,  p = softmax(LM_Head(f)), phat = softmax(LM_Head(fhat))
+ *   L     = L_reg + w_cls * L_cls                                  (the paper sets w_cls = 0.1)
+ *   grad  = dL/dfhat = clip(fhat - f, -1, 1) / (rows * d_model) + w_cls / rows * (phat - p) W_lm_head
+ * f (the target's feature of the next position: the label) and fhat (the head's prediction) are DEVICE pointers to
+ * fp32 [rows, d_model], row-major, only read; the LM head is the one loaded into the context (frozen: it gets no
+ * gradient).  grad_fhat: DEVICE pointer, fp32 [rows, d_model], written (may be null: loss only).  loss_out: HOST
+ * pointer to 3 floats: L, L_reg, L_cls.  Any rows >= 1; the rows are processed in passes of at most half the
+ * context's largest pass each (256 rows for a dense bf16 model).  Leaves the decoding state of the context untouched
+ * (it uses only buffers that live within one pass).  Needs cfg.head_loss_rows > 0 and the LM head loaded
+ * (EAGLE_ESTATE otherwise).  Synchronises the stream (the loss is returned by value). */
+int eagle_head_loss(eagle_ctx *ctx, const float *f_dev, const float *fhat_dev, int32_t rows, float w_cls,
+                    float *grad_fhat_dev, float *loss_out);
+
+/* Data augmentation of Sec. 3.2: out[r][k] = in[r][k] + amplitude * n(r, k), n uniform on (-1, 1): the odd multiples of
+ * 2^-24 drawn by the library's counter-based generator from (seed, step, r, k) -- reproducible, and a different
+ * stream for every step.  fp32 [rows, d_model] DEVICE pointers; in == out is allowed.  The paper's amplitude is 0.1.
+ * Needs no head_loss_rows.  Asynchronous on the context's stream. */
+int eagle_feature_noise(eagle_ctx *ctx, const float *in_dev, float *out_dev, int32_t rows, float amplitude,
+                        uint64_t seed, uint64_t step);
 
 /* Measurement reference, independent of any context: a bare streaming read of `bytes` bytes of device memory
  * (16-byte loads, nothing computed), run `iters` times on `hip_stream`, each launch timed by its own start/stop

@@ -30,7 +30,7 @@ EXPORTS = ["eagle_workspace_bytes", "eagle_init", "eagle_free", "eagle_load_weig
            "eagle_draft_tree", "eagle_verify", "eagle_accept", "eagle_accept_static", "eagle_step", "eagle_vanilla_step", "eagle_generate",
            "eagle_set_hint", "eagle_set_page_table", "eagle_set_buffer", "eagle_force_tree", "eagle_expand_level",
            "eagle_force_accept", "eagle_get_buffer", "eagle_get_kv_row", "eagle_set_profiling", "eagle_get_profile", "eagle_get_kernel_stats", "eagle_probe_stream_read",
-           "eagle_last_error", "eagle_version"]
+           "eagle_head_loss", "eagle_feature_noise", "eagle_last_error", "eagle_version"]
 
 
 class EagleConfig(ctypes.Structure):
@@ -41,7 +41,8 @@ class EagleConfig(ctypes.Structure):
                 ("rope_theta", ctypes.c_float), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
                 ("page_tokens", ctypes.c_int32), ("n_nodes", ctypes.c_int32),
                 ("parent", ctypes.POINTER(ctypes.c_int32)), ("rank", ctypes.POINTER(ctypes.c_int32)),
-                ("temperature", ctypes.c_float), ("seed", ctypes.c_uint64), ("weight_bits", ctypes.c_int32)]
+                ("temperature", ctypes.c_float), ("seed", ctypes.c_uint64), ("weight_bits", ctypes.c_int32),
+                ("head_loss_rows", ctypes.c_int32)]
 
 
 class EagleProfile(ctypes.Structure):
@@ -105,6 +106,8 @@ def load_library(need_gpu_runtime: bool = True):
     lib.eagle_get_profile.argtypes = [vp, ctypes.POINTER(EagleProfile), i32]
     lib.eagle_get_kernel_stats.argtypes = [vp, i32, ctypes.POINTER(EagleKernelStat), i32, pi32, i32]
     lib.eagle_probe_stream_read.argtypes = [vp, sz, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.eagle_head_loss.argtypes = [vp, vp, vp, i32, ctypes.c_float, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.eagle_feature_noise.argtypes = [vp, vp, vp, i32, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64]
     lib.eagle_last_error.restype = ctypes.c_char_p
     lib.eagle_version.restype = ctypes.c_char_p
     _lib = lib
@@ -116,7 +119,7 @@ def _p32(a: Optional[np.ndarray]):
 
 
 def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
-                kv_dtype="fp32", weight_bits=16):
+                kv_dtype="fp32", weight_bits=16, head_loss_rows=0):
     parent = np.ascontiguousarray(parent, dtype=np.int32)
     rank = np.ascontiguousarray(rank, dtype=np.int32)
     cfg = EagleConfig(dtype=EAGLE_F32 if shape.dtype == "fp32" else EAGLE_BF16,
@@ -126,7 +129,7 @@ def make_config(shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=6
                       experts_per_tok=shape.experts_per_tok, draft_moe=int(shape.draft_moe), rms_eps=shape.rms_eps,
                       rope_theta=shape.rope_theta, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
                       n_nodes=len(parent), parent=_p32(parent), rank=_p32(rank), temperature=temperature, seed=seed,
-                      weight_bits=weight_bits)
+                      weight_bits=weight_bits, head_loss_rows=head_loss_rows)
     cfg._keep = (parent, rank)
     return cfg
 
@@ -147,7 +150,7 @@ class Eagle:
     """One libeagle context on cuda:0 (ROCm).  Methods are the C calls, with numpy in/out."""
 
     def __init__(self, shape, parent, rank, *, max_batch=1, max_seq=4096, page_tokens=64, temperature=0.0, seed=0,
-                 kv_dtype="fp32", weight_bits=16, device="cuda:0"):
+                 kv_dtype="fp32", weight_bits=16, head_loss_rows=0, device="cuda:0"):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -155,7 +158,8 @@ class Eagle:
             raise RuntimeError("libeagle needs a GPU (no CPU fallback exists)")
         self.shape, self.device = shape, torch.device(device)
         self.cfg = make_config(shape, parent, rank, max_batch=max_batch, max_seq=max_seq, page_tokens=page_tokens,
-                               temperature=temperature, seed=seed, kv_dtype=kv_dtype, weight_bits=weight_bits)
+                               temperature=temperature, seed=seed, kv_dtype=kv_dtype, weight_bits=weight_bits,
+                               head_loss_rows=head_loss_rows)
         self.weight_bits = weight_bits
         self.M = len(parent)
         depth = [0] * self.M
@@ -190,6 +194,34 @@ class Eagle:
             self.close()
         except Exception:
             pass
+
+    # -- training loss of the head (Sec. 3.2)
+    def head_loss(self, f: np.ndarray, fhat: np.ndarray, w_cls: float = 0.1, want_grad: bool = True):
+        """(L, L_reg, L_cls), dL/dfhat (numpy fp32 [rows, d] or None) for label features f and predictions fhat."""
+        torch = self.torch
+        tf = torch.from_numpy(np.ascontiguousarray(f, dtype=np.float32)).to(self.device)
+        th = torch.from_numpy(np.ascontiguousarray(fhat, dtype=np.float32)).to(self.device)
+        if tf.shape != th.shape or tf.dim() != 2 or tf.shape[1] != self.shape.d_model:
+            raise ValueError("f and fhat must both be [rows, d_model]")
+        tg = torch.empty_like(tf) if want_grad else None
+        out = (ctypes.c_float * 3)()
+        self._chk(self.lib.eagle_head_loss(self.h, tf.data_ptr(), th.data_ptr(), int(tf.shape[0]), float(w_cls),
+                                           tg.data_ptr() if want_grad else None, out))
+        return (float(out[0]), float(out[1]), float(out[2])), (tg.cpu().numpy() if want_grad else None)
+
+    def head_loss_device(self, tf, th, tg, w_cls: float = 0.1):
+        """The same call on tensors already on the device (fp32, contiguous, [rows, d_model]); tg may be None."""
+        out = (ctypes.c_float * 3)()
+        self._chk(self.lib.eagle_head_loss(self.h, tf.data_ptr(), th.data_ptr(), int(tf.shape[0]), float(w_cls),
+                                           tg.data_ptr() if tg is not None else None, out))
+        return float(out[0]), float(out[1]), float(out[2])
+
+    def feature_noise(self, f: np.ndarray, seed: int, step: int, amplitude: float = 0.1) -> np.ndarray:
+        torch = self.torch
+        tf = torch.from_numpy(np.ascontiguousarray(f, dtype=np.float32)).to(self.device)
+        self._chk(self.lib.eagle_feature_noise(self.h, tf.data_ptr(), tf.data_ptr(), int(tf.shape[0]), float(amplitude), int(seed), int(step)))
+        self.torch.cuda.synchronize(self.device)
+        return tf.cpu().numpy()
 
     # -- weights
     def load_weight(self, which: int, layer: int, host: np.ndarray) -> None:

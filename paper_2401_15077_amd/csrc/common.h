@@ -60,7 +60,7 @@ __host__ __device__ inline size_t xf_index(int m, int k, int plane, int MT, int 
 
 // ---------------------------------------------------------------- counter-based uniforms (24-bit)
 #define EAGLE_GOLDEN 0x9E3779B97F4A7C15ull
-enum { PURPOSE_ACCEPT = 1, PURPOSE_FINAL = 2, PURPOSE_GUMBEL = 3, PURPOSE_HINT = 4 };
+enum { PURPOSE_ACCEPT = 1, PURPOSE_FINAL = 2, PURPOSE_GUMBEL = 3, PURPOSE_HINT = 4, PURPOSE_NOISE = 5 };
 __host__ __device__ inline uint64_t mix64(uint64_t x) {
   x += EAGLE_GOLDEN;
   x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;

@@ -117,6 +117,9 @@ struct eagle_ctx {
   int n_cu = 256;                      // compute units of the device (queried by eagle_init; 256 assumed when no device is visible)
   int device = 0;
   void* static_scratch = nullptr;      // this device's address of the library's static scratch array
+  // training loss of the head (cfg.head_loss_rows > 0): the LM head re-tiled as [d_model rows][vocab columns], the
+  // gradient of one pass's logits as a GEMM input, per-row losses of a pass, the running sums of a call
+  PackedW lm_head_T; bf16_t* hl_dz = nullptr; float* hl_row_loss = nullptr; double* hl_acc = nullptr; int hl_chunk = 0;
   // host mirror
   std::vector<int> h_ctx, h_ntok; std::vector<char> active, head_stale;
   int n_active = 0;
@@ -151,7 +154,8 @@ static GemmPlan plan_pf(int NRB, int KS, int MT, int n_cu) {
   GemmPlan p;
   const int wgs = ((NRB + 7) / 8) * ((MT + 3) / 4);
   // one tile of rows (a batched tree pass): the weights are streamed once, so deeper splits pay for themselves
-  int S = wgs * 2 > n_cu ? 1 : std::min(MT <= 4 ? 16 : 4, n_cu / std::max(1, wgs));
+  // (a very long K -- the product with the transposed LM head -- affords 8)
+  int S = wgs * 2 > n_cu ? 1 : std::min(MT <= 4 ? 16 : KS >= 1024 ? 8 : 4, n_cu / std::max(1, wgs));
   S = std::max(1, std::min(S, KS / (MT <= 4 ? 16 : 32)));
   p.ks_per_split = ((KS + S - 1) / S + 3) / 4 * 4;
   p.S = (KS + p.ks_per_split - 1) / p.ks_per_split;
@@ -286,6 +290,12 @@ static size_t layout(eagle_ctx* c) {
   // weights
   c->embed = a.take<char>((size_t)V * d * c->elt);
   take_packed(a, c->lm_head, V, d, c->NWP, c->q4);
+  if (g.head_loss_rows > 0) {
+    take_packed(a, c->lm_head_T, d, V, c->NWP);
+    c->hl_dz = a.take<bf16_t>((size_t)c->NXP * c->hl_chunk * V);
+    c->hl_row_loss = a.take<float>((size_t)2 * c->hl_chunk);
+    c->hl_acc = a.take<double>(2);
+  }
   take_packed(a, c->fc, d, 2 * d, c->NWP, c->q4);
   c->final_norm = a.take<float>(d);
   c->fc_bias = a.take<float>(d);
@@ -354,6 +364,7 @@ static size_t layout(eagle_ctx* c) {
     }
   };
   consider(c->lm_head); consider(c->fc);
+  if (g.head_loss_rows > 0) consider(c->lm_head_T);
   for (auto& w : c->layers) {
     consider(w.qkv); consider(w.o);
     if (w.moe) { consider(w.e_gu[0]); consider(w.e_dn[0]); } else { consider(w.gu); consider(w.dn); }
@@ -431,6 +442,13 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   }
   int rows = std::max(c->pf_chunk, cfg->max_batch * c->M);
   c->Mmax = (rows + 31) / 32 * 32;
+  if (cfg->head_loss_rows < 0) return fail(EAGLE_EINVAL, "head_loss_rows must be >= 0");
+  if (cfg->head_loss_rows > 0) {
+    if (c->f32 || c->q4) return fail(EAGLE_EINVAL, "head_loss_rows > 0 needs a bf16 model with its weights as given");
+    if (cfg->vocab % 64) return fail(EAGLE_EINVAL, "head_loss_rows > 0 needs vocab to be a multiple of 64");
+    c->hl_chunk = c->Mmax / 2 / 32 * 32;          // label rows and prediction rows share one pass of the LM head
+    if (c->hl_chunk < 32) return fail(EAGLE_EINVAL, "internal: no room for a loss pass");
+  }
   return EAGLE_OK;
 }
 
@@ -563,7 +581,16 @@ extern "C" int eagle_load_weight(eagle_ctx* c, int32_t which, int32_t layer, con
   if (which < EAGLE_W_ATTN_NORM) {
     switch (which) {
       case EAGLE_W_EMBED: HIPCHK(hipMemcpyAsync(c->embed, src, (size_t)g.vocab * d * c->elt, hipMemcpyDeviceToDevice, c->stream)); break;
-      case EAGLE_W_LM_HEAD: rc = pack_into(c, src, c->lm_head, g.vocab, d, 0); break;
+      case EAGLE_W_LM_HEAD:
+        rc = pack_into(c, src, c->lm_head, g.vocab, d, 0);
+        if (!rc && g.head_loss_rows > 0) {        // W^T for the gradient: row n = column n of the LM head, K = vocab
+          PackedW& t = c->lm_head_T;
+          const size_t total = (size_t)t.NRB * t.KS * 64;
+          k_pack_weight<bf16_t><<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>((const bf16_t*)src, t.w, d, g.vocab, 0, t.KS, c->NWP, t.plane_stride,
+                                                                                      PACK_PLAIN, g.head_dim, (size_t)1, (size_t)d);
+          if (hipGetLastError() != hipSuccess) rc = fail(EAGLE_EHIP, "LM head transpose launch failed");
+        }
+        break;
       case EAGLE_W_FINAL_NORM: HIPCHK(hipMemcpyAsync(c->final_norm, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
       case EAGLE_W_FC: rc = pack_into(c, src, c->fc, d, 2 * d, 0); break;
       case EAGLE_W_FC_BIAS: HIPCHK(hipMemcpyAsync(c->fc_bias, src, (size_t)d * 4, hipMemcpyDeviceToDevice, c->stream)); break;
@@ -1186,6 +1213,60 @@ extern "C" int eagle_prefill(eagle_ctx* c, int32_t seq, const int32_t* prompt, i
   if (first_token) *first_token = tok;
   c->h_ctx[seq] = n; c->h_ntok[seq] = n + 1; c->active[seq] = 1; c->head_stale[seq] = 0;
   c->n_active = seq + 1; c->phase = 0;
+  return EAGLE_OK;
+}
+
+// ---------------------------------------------------------------------------- training loss of the head (Sec. 3.2)
+extern "C" int eagle_head_loss(eagle_ctx* c, const float* f, const float* fhat, int32_t rows, float w_cls, float* grad, float* loss_out) {
+  if (!c || !f || !fhat || !loss_out) return fail(EAGLE_EINVAL, "null argument");
+  const eagle_config& g = c->cfg;
+  if (g.head_loss_rows <= 0) return fail(EAGLE_ESTATE, "the context was created without head_loss_rows");
+  if (!c->loaded_layer[EAGLE_W_LM_HEAD][0]) return fail(EAGLE_ESTATE, "the LM head was never loaded");
+  if (rows < 1) return fail(EAGLE_EINVAL, "rows must be >= 1");
+  if (!(w_cls >= 0.f)) return fail(EAGLE_EINVAL, "w_cls must be >= 0");
+  const int d = g.d_model, V = g.vocab;
+  k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->hl_acc, 0u, (size_t)4);
+  LAUNCH_CHECK();
+  const float cls_scale = w_cls / (float)rows, reg_scale = 1.0f / ((float)rows * (float)d);
+  for (int r0 = 0; r0 < rows; r0 += c->hl_chunk) {
+    const int rc_ = std::min(c->hl_chunk, rows - r0), rpad = (rc_ + 31) / 32 * 32;
+    const int MTf = 2 * rpad / 32, MTb = rpad / 32;
+    if (MTf * 32 > c->Mmax) return fail(EAGLE_EINVAL, "internal: loss pass of %d rows exceeds the pass limit", MTf * 32);
+    // labels in rows [0, rc_), predictions in rows [rpad, rpad + rc_) of one LM-head pass
+    k_rows_to_xf<<<dim3(rc_, 2), 256, 0, c->stream>>>(f + (size_t)r0 * d, 0, c->xf_d, MTf, c->NXP, d);
+    LAUNCH_CHECK();
+    k_rows_to_xf<<<dim3(rc_, 2), 256, 0, c->stream>>>(fhat + (size_t)r0 * d, rpad, c->xf_d, MTf, c->NXP, d);
+    LAUNCH_CHECK();
+    int S, rc;
+    if ((rc = (c->cur_class = KC_LMHEAD, gemm(c, c->lm_head, c->xf_d, MTf, &S)))) return rc;
+    auto loss_row = V <= 4 * 8192 ? k_head_loss_row<4> : k_head_loss_row<0>;   // larger vocabularies would spill: they stream
+    loss_row<<<rc_, 1024, 0, c->stream>>>(c->PT, S, MTf * 32, c->lm_head.Npad, rpad, V, f + (size_t)r0 * d, fhat + (size_t)r0 * d, d,
+                                          cls_scale, reg_scale, c->hl_dz, MTb, c->NXP, grad ? grad + (size_t)r0 * d : nullptr, c->hl_row_loss);
+    LAUNCH_CHECK();
+    k_head_loss_accumulate<<<1, 64, 0, c->stream>>>(c->hl_row_loss, rc_, c->hl_acc);
+    LAUNCH_CHECK();
+    if (grad) {
+      if ((rc = (c->cur_class = KC_LMHEAD, gemm(c, c->lm_head_T, c->hl_dz, MTb, &S)))) return rc;
+      k_head_loss_grad_finish<<<dim3((d + 255) / 256, rc_), 256, 0, c->stream>>>(c->PT, S, MTb * 32, c->lm_head_T.Npad, grad + (size_t)r0 * d, d);
+      LAUNCH_CHECK();
+    }
+  }
+  double acc[2] = {0.0, 0.0};
+  HIPCHK(hipMemcpyAsync(acc, c->hl_acc, sizeof(acc), hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(hipStreamSynchronize(c->stream));
+  const double L_reg = acc[0] / ((double)rows * (double)d), L_cls = acc[1] / (double)rows;
+  loss_out[0] = (float)(L_reg + (double)w_cls * L_cls); loss_out[1] = (float)L_reg; loss_out[2] = (float)L_cls;
+  return EAGLE_OK;
+}
+
+extern "C" int eagle_feature_noise(eagle_ctx* c, const float* in, float* out, int32_t rows, float amplitude, uint64_t seed, uint64_t step) {
+  if (!c || !in || !out) return fail(EAGLE_EINVAL, "null argument");
+  if (rows < 1) return fail(EAGLE_EINVAL, "rows must be >= 1");
+  if (!(amplitude >= 0.f)) return fail(EAGLE_EINVAL, "amplitude must be >= 0");
+  const size_t n = (size_t)rows * c->cfg.d_model;
+  const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 4096);
+  k_feature_noise<<<blocks, 256, 0, c->stream>>>(in, out, rows, c->cfg.d_model, amplitude, rng_prefix(seed, PURPOSE_NOISE, step));
+  LAUNCH_CHECK();
   return EAGLE_OK;
 }
 

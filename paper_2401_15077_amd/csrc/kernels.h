@@ -164,7 +164,9 @@ __host__ __device__ inline int pack_row_map(int mode, int n, int dh) {
 }
 template <typename SrcT>
 __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ src, bf16_t* __restrict__ dst, int N, int K,
-                                                     int row_offset, int KS, int nplanes, size_t plane_stride, int mode, int dh) {
+                                                     int row_offset, int KS, int nplanes, size_t plane_stride, int mode, int dh,
+                                                     size_t ldn = 0 /*source stride between rows n (0 = K)*/, size_t ldk = 1 /*between columns k*/) {
+  if (ldn == 0) ldn = (size_t)K;
   size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   int nrb = (N + 31) >> 5;
   size_t total = (size_t)nrb * KS * 64;
@@ -180,8 +182,8 @@ __global__ __launch_bounds__(256) void k_pack_weight(const SrcT* __restrict__ sr
   for (int t = 0; t < 8; ++t) {
     float x = 0.f;
     if (n < N && k0 + t < K) {
-      if constexpr (sizeof(SrcT) == 4) x = ((const float*)src)[(size_t)n * K + k0 + t];
-      else x = bf16_to_f32(((const bf16_t*)src)[(size_t)n * K + k0 + t]);
+      if constexpr (sizeof(SrcT) == 4) x = ((const float*)src)[(size_t)n * ldn + (size_t)(k0 + t) * ldk];
+      else x = bf16_to_f32(((const bf16_t*)src)[(size_t)n * ldn + (size_t)(k0 + t) * ldk]);
     }
     bf16_t p[3];
     split_bf16(x, p, nplanes);
@@ -724,6 +726,149 @@ __global__ __launch_bounds__(256) void k_store_rows(Pass pass, const TreeDev* tr
   } else if (pass.kind == PASS_VANILLA) dst = pend_dst + (size_t)ri.seq * (tree->D + 1) * d;
   if (!dst) return;
   for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = src[(size_t)r * d + k];
+}
+
+// ============================================================================ training loss of the head (Sec. 3.2)
+// Rows of fp32 features -> rows [row0, row0 + rows) of a GEMM input of MT 32-row tiles (XF layout).  Grid (rows, parts).
+__global__ __launch_bounds__(256) void k_rows_to_xf(const float* __restrict__ src, int row0, bf16_t* XF, int MT, int nplanes, int d) {
+  const int r = blockIdx.x;
+  for (int k8 = (blockIdx.y * blockDim.x + threadIdx.x) * 8; k8 < d; k8 += gridDim.y * blockDim.x * 8) {
+    float x[8];
+    const f32x4 a = *(const f32x4*)(src + (size_t)r * d + k8), b = *(const f32x4*)(src + (size_t)r * d + k8 + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    xf_store8(XF, row0 + r, k8, MT, d / 16, nplanes, x);
+  }
+}
+
+// One row of the loss (block = row r of the pass).  Z holds the LM head's logits of the pass as S split-K partials
+// PT[s][m][n]: row r = logits of the label feature f, row zh_row0 + r = logits of the prediction fhat.
+//   p = softmax(z), q = softmax(zh);  cross entropy of the row = lse(zh) - sum_v p_v zh_v
+//   dZ[r][v] = (q_v - p_v) * cls_scale            (cls_scale = w_cls / rows of the whole call), written as GEMM input
+//   Smooth L1 of the row over d columns (threshold 1), its derivative clip(x, -1, 1) * reg_scale -> grad[r][:]
+// row_loss[r] = (sum of the row's smooth-L1 terms, the row's cross entropy); means are taken by the caller.
+// NCH > 0: a thread keeps its NCH chunks of 8 logits of both rows in registers (V <= 8192 * NCH), so the logits are
+// read once; NCH = 0: any V, three passes over the logits.
+template <int NCH>
+__global__ __launch_bounds__(1024) void k_head_loss_row(const float* __restrict__ Z, int S, int Mpad, int Npad, int zh_row0, int V,
+                                                        const float* __restrict__ f, const float* __restrict__ fhat, int d,
+                                                        float cls_scale, float reg_scale, bf16_t* DZ, int MT, int nplanes,
+                                                        float* grad /*[rows][d] or null*/, float* row_loss /*[rows][2]*/) {
+  __shared__ float sh[16];
+  const int r = blockIdx.x;
+  auto load8 = [&](int row, int v8, float* x) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < S; ++s) {
+      const float* src = Z + ((size_t)s * Mpad + row) * Npad + v8;
+      const f32x4 a1 = *(const f32x4*)src, b1 = *(const f32x4*)(src + 4);
+      a += a1; b += b1;
+    }
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  };
+  constexpr int NR = NCH > 0 ? NCH : 1;
+  float zr[NR][8], hr[NR][8];
+  float mz = -INFINITY, mh = -INFINITY;
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int v8 = (c * 1024 + (int)threadIdx.x) * 8;
+      if (v8 < V) {
+        load8(r, v8, zr[c]); load8(zh_row0 + r, v8, hr[c]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { mz = fmaxf(mz, zr[c][t]); mh = fmaxf(mh, hr[c][t]); }
+      }
+    }
+  } else {
+    for (int v8 = threadIdx.x * 8; v8 < V; v8 += blockDim.x * 8) {
+      load8(r, v8, zr[0]); load8(zh_row0 + r, v8, hr[0]);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) { mz = fmaxf(mz, zr[0][t]); mh = fmaxf(mh, hr[0][t]); }
+    }
+  }
+  mz = block_max(mz, sh);
+  mh = block_max(mh, sh);
+  float sz = 0.f, shh = 0.f, dot = 0.f;
+  auto sums8 = [&](const float* z, const float* zh) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float e = __expf(z[t] - mz);
+      sz += e; shh += __expf(zh[t] - mh); dot += e * (zh[t] - mh);
+    }
+  };
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+      if ((c * 1024 + (int)threadIdx.x) * 8 < V) sums8(zr[c], hr[c]);
+  } else {
+    for (int v8 = threadIdx.x * 8; v8 < V; v8 += blockDim.x * 8) { load8(r, v8, zr[0]); load8(zh_row0 + r, v8, hr[0]); sums8(zr[0], hr[0]); }
+  }
+  sz = block_sum(sz, sh);
+  shh = block_sum(shh, sh);
+  dot = block_sum(dot, sh);
+  const float cls = logf(shh) - dot / sz;                          // lse(zh) - sum_v p_v zh_v, both taken relative to mh
+  const float isz = 1.0f / sz, ish = 1.0f / shh;
+  auto store8 = [&](int v8, const float* z, const float* zh) {
+    float x[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] = (__expf(zh[t] - mh) * ish - __expf(z[t] - mz) * isz) * cls_scale;
+    xf_store8(DZ, r, v8, MT, V / 16, nplanes, x);
+  };
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int v8 = (c * 1024 + (int)threadIdx.x) * 8;
+      if (v8 < V) store8(v8, zr[c], hr[c]);
+    }
+  } else {
+    for (int v8 = threadIdx.x * 8; v8 < V; v8 += blockDim.x * 8) { load8(r, v8, zr[0]); load8(zh_row0 + r, v8, hr[0]); store8(v8, zr[0], hr[0]); }
+  }
+  float reg = 0.f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    const float x = fhat[(size_t)r * d + k] - f[(size_t)r * d + k];
+    const float ax = fabsf(x);
+    reg += ax < 1.0f ? 0.5f * x * x : ax - 0.5f;
+    if (grad) grad[(size_t)r * d + k] = fminf(fmaxf(x, -1.0f), 1.0f) * reg_scale;
+  }
+  reg = block_sum(reg, sh);
+  if (threadIdx.x == 0) { row_loss[2 * r] = reg; row_loss[2 * r + 1] = cls; }
+}
+
+// grad[r][k] += sum over the S split-K partials of (dZ W)[r][k]   (the classification part of the gradient)
+__global__ __launch_bounds__(256) void k_head_loss_grad_finish(const float* __restrict__ PT, int S, int Mpad, int Npad, float* grad, int d) {
+  const int r = blockIdx.y, k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= d) return;
+  float a = 0.f;
+  for (int s = 0; s < S; ++s) a += PT[((size_t)s * Mpad + r) * Npad + k];
+  grad[(size_t)r * d + k] += a;
+}
+
+// acc[0] += sum of the rows' smooth-L1 sums, acc[1] += sum of the rows' cross entropies, in fp64 and in a fixed order:
+// lane l of one wave adds rows l, l + 64, ...; lane 0 then adds the 64 lane sums in lane order.
+__global__ __launch_bounds__(64) void k_head_loss_accumulate(const float* row_loss, int rows, double* acc) {
+  __shared__ double sa[64], sb[64];
+  double a = 0.0, b = 0.0;
+  for (int r = threadIdx.x; r < rows; r += 64) { a += (double)row_loss[2 * r]; b += (double)row_loss[2 * r + 1]; }
+  sa[threadIdx.x] = a; sb[threadIdx.x] = b;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double ta = acc[0], tb = acc[1];
+    for (int l = 0; l < 64; ++l) { ta += sa[l]; tb += sb[l]; }
+    acc[0] = ta; acc[1] = tb;
+  }
+}
+
+// out = in + amplitude * n, n = the odd multiple of 2^-24 in (-1, 1) that the counter-based generator draws for
+// (row, column); the product and the sum are rounded separately (no fused multiply-add), so the result is the same
+// bits wherever it is computed.
+__global__ __launch_bounds__(256) void k_feature_noise(const float* in, float* out, int rows, int d, float amplitude, unsigned long long prefix) {
+#pragma clang fp contract(off)
+  const size_t n = (size_t)rows * d;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t r = (uint32_t)(i / d), k = (uint32_t)(i % d);
+    const int k24 = (int)rng_u24(prefix, r >> 16, r & 0xFFFFu, k);
+    const float u = (float)(2 * (k24 - (1 << 23)) + 1) * 5.9604644775390625e-8f;
+    const float prod = amplitude * u;
+    out[i] = in[i] + prod;
+  }
 }
 
 // ============================================================================ token choice
