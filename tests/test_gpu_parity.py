@@ -156,7 +156,8 @@ def test_moe_twin_bf16_lockstep():
 
 def test_batch4_lockstep():
     """Four independent sequences (different prompt lengths) advance together: the head's passes put the rows of all
-    slots through the same GEMMs; the 4 x 15 verify rows exceed one 32-row pass and are verified slot by slot."""
+    slots through the same GEMMs; the 4 x 15 verify rows exceed one 32-row pass and go through the general path
+    together (one 60-row pass); every slot is compared with its own oracle."""
     s = synth.SHAPES["tiny"]
     par, rk = synth.TREES["T15"]
     eng = pkg.Eagle(s, par, rk, max_batch=4, max_seq=160)
