@@ -83,6 +83,10 @@ struct eagle_ctx {
   char* ws; size_t ws_bytes;
   bool f32, kv_f32, q4 = false;      // q4: weight matrices stored in 4 bits (fast path only)
   bool q4_staged = true;
+  // 4-bit weights: epilogue classes (1 << epi) that take the streamed split-K kernel.  Measured at d = 4096 (us, streamed
+  // split-K against the alternative): O 13.8 / 15.3 and down 20.8 / 26.7 and FC 16.3 / 20.0 (LDS-staged split-K, whose
+  // 128 KB slice limit forces 11 slices at K = 11008); QKV 26.3 / 21.7 (whole-K): the residual epilogue only.
+  int q4_xk_mask = 1 << EPI_RESID;
   int NWP, NXP, elt, kv_elt;         // weight planes, activation planes, bytes per weight / per KV element
   TreeDev tree_h; TreeDev* tree_d;
   int M, D, Mmax, max_level_rows;
@@ -530,6 +534,7 @@ extern "C" int eagle_init(const eagle_config* cfg, void* workspace_dev, size_t w
   memset(&c->prof, 0, sizeof(c->prof));
 #ifdef EAGLE_TRACE
   if (const char* t = getenv("EAGLE_Q4_STAGED")) c->q4_staged = atoi(t) != 0;
+  if (const char* t = getenv("EAGLE_Q4_XK")) c->q4_xk_mask = atoi(t);
   if (const char* t = getenv("EAGLE_GEMM_TRACE")) c->trace_sel = atoi(t);
   if (const char* t = getenv("EAGLE_ATTN_TRACE")) c->attn_trace_sel = atoi(t);
   if (getenv("EAGLE_EXPAND_TRACE")) c->expand_trace = 1;
@@ -930,6 +935,33 @@ static hipError_t launch_xk(eagle_ctx* c, double bytes, const Gemm2& g) {
   return launch_k(c, c->cur_class, bytes, "k2_gemm_xk", k2_gemm_xk<1, 2, NRMAX>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
 }
 
+template <int NRMAX>
+static hipError_t launch_xk_q4(eagle_ctx* c, double bytes, const Gemm2& g) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)8 * NRMAX * 4096;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k2_gemm_xk<1, 2, NRMAX, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  return launch_k(c, c->cur_class, bytes, "k2_gemm_xk<4-bit weights>", k2_gemm_xk<1, 2, NRMAX, true>, dim3(g.groups * g.S), dim3(V2_THREADS), lds, g);
+}
+
+// Work split of the streamed split-K kernel for 4-bit weights: slices of whole groups, at least one group per wave, at
+// most 3 row blocks per work-group (registers); same cost form as plan_xk with the weights at a quarter of the bytes.
+static PlanXK plan_xk_q4(int NRB, int NG, int NXP, int n_cu, size_t pt_floats_per_slice, size_t pt_floats) {
+  PlanXK best; best.S = 0; best.groups = 0; best.nrmax = 0; best.cost = -1;
+  for (int S = 1; S <= 16; ++S) {
+    const int groups = std::min(NRB, n_cu / S);
+    if (groups < 1 || NG / S < 8) break;
+    const int nrm = (NRB + groups - 1) / groups, kt = 8 * ((NG + S - 1) / S);
+    if (nrm > 3 || (size_t)S * pt_floats_per_slice > pt_floats) continue;
+    const long cost = (long)nrm * kt / 4 + (long)NXP * kt * 4 / 5 + 2L * S * nrm * 4;
+    if (best.cost < 0 || cost < best.cost) { best.S = S; best.groups = groups; best.nrmax = nrm; best.cost = cost; }
+  }
+  return best;
+}
+
 // Runs one fused GEMM: g carries the epilogue description; the matrix, the input and the work split are filled here.
 static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int* groups_out) {
   Plan2 p = plan2(w.NRB, w.KS, c->NXP, c->NWP, c->n_cu, w.q4);
@@ -945,11 +977,24 @@ static int gemm2(eagle_ctx* c, const PackedW& w, const bf16_t* XF, Gemm2& g, int
   if (groups_out) *groups_out = p.groups;
   const double bytes = w.bytes(c->elt);
   hipError_t e;
+  if (w.q4 && ((c->q4_xk_mask >> g.epi) & 1)) {
+    const PlanXK px = plan_xk_q4(w.NRB, w.NG, c->NXP, c->n_cu, (size_t)w.Npad * 32, c->pt2_floats);
+    if (px.S > 0) {
+      g.S = px.S; g.groups = px.groups; g.SC = w.sc; g.NG = w.NG;
+      g.trace = nullptr;
+      if (groups_out) *groups_out = px.groups;
+      if (g.ssq_out && px.groups > 256) return fail(EAGLE_EINVAL, "internal: more than 256 row groups feed a norm");
+      e = px.nrmax <= 1 ? launch_xk_q4<1>(c, bytes, g) : px.nrmax == 2 ? launch_xk_q4<2>(c, bytes, g) : launch_xk_q4<3>(c, bytes, g);
+      if (e != hipSuccess) return fail(EAGLE_EHIP, "4-bit gemm launch failed: %s", hipGetErrorString(e));
+      return EAGLE_OK;
+    }
+  }
   if (w.q4 && c->q4_staged && (g.epi == EPI_RESID || (w.NRB + 2) / 3 > c->n_cu)) {   // (or too many row blocks for one round of whole-K work-groups: the LM head)
-    // 4-bit weights, narrow matrices (O, down, FC): split-K with the activation slice staged in LDS.  With a quarter of
-    // the weight bytes the activation fragments are most of what a CU fetches; staged, a work-group fetches its K slice of
-    // them once.  (Measured at d = 4096: O 13.9 us against 15.0 whole-K, down 25.5 against 29.8, FC 18.9 against 21.8;
-    // the wide matrices are faster whole-K: QKV 20.2 against 27.3 -- their epilogues would run on 64 CUs only.)
+    // 4-bit weights, the LM head (and narrow matrices the streamed split-K plan cannot take): split-K with the activation
+    // slice staged in LDS.  With a quarter of the weight bytes the activation fragments are most of what a CU fetches;
+    // staged, a work-group fetches its K slice of them once.  (Measured at d = 4096: O 13.9 us against 15.0 whole-K, down
+    // 25.5 against 29.8, FC 18.9 against 21.8; the wide matrices are faster whole-K: QKV 20.2 against 27.3 -- their
+    // epilogues would run on 64 CUs only.)
     g.SC = w.sc; g.NG = w.NG;
     g.trace = nullptr;
     switch (p.RW) {

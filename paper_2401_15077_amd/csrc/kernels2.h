@@ -1038,8 +1038,10 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_fk(Gemm2 g) {
 // blocks each.  The work-group then costs its weights plus M/32 of its X slice in fetches, but exchanges only
 // S x (row blocks) x 4 KiB per row group, and nothing waits for an LDS fill before the weight stream starts.
 // Partials, arrival counter and epilogues are those of k2_gemm.
-template <int NWP, int NXP, int NRMAX>
+// Q4: 4-bit codes (k_pack_weight_q4); the slices are then whole groups of 128 columns (host: at least 8 groups a slice).
+template <int NWP, int NXP, int NRMAX, bool Q4 = false>
 __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
+  static_assert(!Q4 || NWP == 1, "4-bit weights: one plane");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sh_small[16 * 33];
   __shared__ float rstd_s[32];
@@ -1077,6 +1079,20 @@ __global__ __launch_bounds__(V2_THREADS) void k2_gemm_xk(Gemm2 g) {
       }
     }
   }
+  if constexpr (Q4) {
+    const unsigned uNG = g.NG;
+    const int G0 = (unsigned)s * uNG / uS, G1 = (unsigned)(s + 1) * uNG / uS, gt = G1 - G0;
+    const int gb = G0 + (unsigned)w * (unsigned)gt / 8u, ge = G0 + (unsigned)(w + 1) * (unsigned)gt / 8u;
+    const u32x4* wq[NRMAX];
+    const u32x4* sq[NRMAX];
+#pragma unroll
+    for (int j = 0; j < NRMAX; ++j) {
+      const size_t rb = (size_t)min(rb0 + j, g.NRB - 1);
+      wq[j] = (const u32x4*)g.W + rb * (size_t)(g.KS / 4) * 64 + lane;
+      sq[j] = (const u32x4*)g.SC + rb * (size_t)g.NG * 4 + 2 * (lane >> 5);
+    }
+    fk_stream_q4_dispatch<NXP, NRMAX>(nr, g.XF, g.KS, g.M, gb, ge, wq, sq, g.NG, acc, lane);
+  } else
   fk_stream_dispatch<NWP, NXP, NRMAX>(nr, g.XF, g.KS, g.M, kb, ke, wp, g.wps, acc, lane);
   TRACE_STAMP_AFTER(tr, 2, acc[0][0]);
 #pragma unroll
