@@ -767,9 +767,9 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   KVCache kv = kv_for(c, li);
   if ((rc = (c->cur_class = KC_QKV, gemm(c, w.qkv, c->xf_d, MT, &S)))) return rc;
   {
-    dim3 grid(M, H + 2 * KVH);
-    if (c->kv_f32) k_qkv_rope_store<float><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
-    else k_qkv_rope_store<bf16_t><<<grid, 64, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
+    dim3 grid(M, (H + 2 * KVH + 3) / 4);
+    if (c->kv_f32) k_qkv_rope_store<float><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
+    else k_qkv_rope_store<bf16_t><<<grid, 256, 0, c->stream>>>(pass, c->tree_d, c->st, c->PT, S, w.qkv.Npad, MT * 32, c->rope_cos, c->rope_sin, c->Q, kv, H);
     LAUNCH_CHECK();
   }
   {
@@ -808,8 +808,8 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
       if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.e_gu[e], c->xf_d, MT, &S)))) return rc;
-      dim3 grid((F / 8 + 255) / 256, M);
-      k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.e_gu[e].Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
+      dim3 grid((F / 16 + 3) / 4, MT);
+      k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.e_gu[e].Npad, MT * 32, F, M, c->xf_ffn, MT, c->NXP);
       LAUNCH_CHECK();
       if ((rc = (c->cur_class = KC_DOWN, gemm(c, w.e_dn[e], c->xf_ffn, MT, &S)))) return rc;
       const bool last = e + 1 == E;     // only the last expert's pass produces the normalised output
@@ -820,8 +820,8 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
   }
   if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.gu, c->xf_d, MT, &S)))) return rc;
   {
-    dim3 grid((F / 8 + 255) / 256, M);
-    k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, c->xf_ffn, MT, c->NXP);
+    dim3 grid((F / 16 + 3) / 4, MT);
+    k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, M, c->xf_ffn, MT, c->NXP);
     LAUNCH_CHECK();
   }
   if ((rc = (c->cur_class = KC_DOWN, gemm(c, w.dn, c->xf_ffn, MT, &S)))) return rc;

@@ -574,9 +574,12 @@ __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float*
   __shared__ float sh[16];
   int r = blockIdx.x;
   float ss = 0.f;
-  // each thread owns chunks of 8 consecutive k
+  // each thread owns chunks of 8 consecutive k; the first four chunks (rows of up to 8192 columns) stay in registers
+  // for the second phase, further ones are read back from h_out
+  constexpr int KEEP = 4;
+  float keep[KEEP][8];
   const float rw = row_w ? row_w[r] : 1.0f;    // MoE: this expert's routing weight for the row (0 = not routed here)
-  for (int k8 = threadIdx.x * 8; k8 < d; k8 += blockDim.x * 8) {
+  auto phase1 = [&](int k8, float* v) {
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (PT) {
       for (int s0 = 0; s0 < S; s0 += 8) {        // eight splits' worth of loads in flight, added in split order
@@ -597,38 +600,59 @@ __global__ __launch_bounds__(256) void k_resnorm(const float* h_in, const float*
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       int k = k8 + t;
-      float v = h_in ? h_in[(size_t)r * d + k] : 0.f;
-      if (PT) v += row_w ? rw * a[t] : a[t];
-      if (bias) v += bias[k];
-      h_out[(size_t)r * d + k] = v;
-      ss += v * v;
+      float x = h_in ? h_in[(size_t)r * d + k] : 0.f;
+      if (PT) x += row_w ? rw * a[t] : a[t];
+      if (bias) x += bias[k];
+      h_out[(size_t)r * d + k] = x;
+      ss += x * x;
+      v[t] = x;
     }
+  };
+#pragma unroll
+  for (int it = 0; it < KEEP; ++it) {
+    const int k8 = (it * (int)blockDim.x + (int)threadIdx.x) * 8;
+    if (k8 < d) phase1(k8, keep[it]);
   }
+  for (int k8 = (KEEP * blockDim.x + threadIdx.x) * 8; k8 < d; k8 += blockDim.x * 8) { float v[8]; phase1(k8, v); }
   ss = block_sum(ss, sh);
   float rstd = gain ? 1.0f / sqrtf(ss / (float)d + eps) : 1.0f;
   const int KS = d / 16;
-  for (int k8 = threadIdx.x * 8; k8 < d; k8 += blockDim.x * 8) {
+  auto phase2 = [&](int k8, const float* v) {
     float x[8];
+#pragma unroll
     for (int t = 0; t < 8; ++t) {
-      float v = h_out[(size_t)r * d + k8 + t];
-      x[t] = gain ? v * rstd * gain[k8 + t] : v;
+      x[t] = gain ? v[t] * rstd * gain[k8 + t] : v[t];
       if (xout) xout[(size_t)r * d + k8 + t] = x[t];
     }
     if (XF) xf_store8(XF, r, k8, MT, KS, nplanes, x);
+  };
+  if (!XF && !xout) return;
+#pragma unroll
+  for (int it = 0; it < KEEP; ++it) {
+    const int k8 = (it * (int)blockDim.x + (int)threadIdx.x) * 8;
+    if (k8 < d) phase2(k8, keep[it]);
+  }
+  for (int k8 = (KEEP * blockDim.x + threadIdx.x) * 8; k8 < d; k8 += blockDim.x * 8) {
+    float v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = h_out[(size_t)r * d + k8 + t];
+    phase2(k8, v);
   }
 }
 
 // q, k, v = rows of PT (the fused QKV projection); rotate-half RoPE on q and k with the row's position id;
-// q -> Q[r][head][dh] fp32, k and v -> this layer's paged cache at the row's slot.  Block = one (row, head).
+// q -> Q[r][head][dh] fp32, k and v -> this layer's paged cache at the row's slot.
 template <typename CT>
-__global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev* tree, SeqState st,
-                                                       const float* __restrict__ PT, int S, int Npad, int Mpad,
-                                                       const float* __restrict__ rope_cos, const float* __restrict__ rope_sin,
-                                                       float* Q, KVCache kv, int H) {
-  int r = blockIdx.x, hd = blockIdx.y;
-  RowInfo ri = row_info(pass, tree, st, r);
+__global__ __launch_bounds__(256) void k_qkv_rope_store(Pass pass, const TreeDev* tree, SeqState st,
+                                                        const float* __restrict__ PT, int S, int Npad, int Mpad,
+                                                        const float* __restrict__ rope_cos, const float* __restrict__ rope_sin,
+                                                        float* Q, KVCache kv, int H) {
+  // a wave per (row, head); four heads per block
+  const int r = blockIdx.x, hd = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int dh = kv.head_dim, half = dh >> 1, KVH = kv.n_kv_heads;
-  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+  if (hd >= H + 2 * KVH) return;
+  RowInfo ri = row_info(pass, tree, st, r);
+  for (int i = threadIdx.x & 63; i < half; i += 64) {
     // q/k heads are packed with rotate-half partners adjacent (PACK_ROPE); v heads keep their order
     int n1 = hd < H + KVH ? hd * dh + 2 * i : hd * dh + i;
     int n2 = hd < H + KVH ? n1 + 1 : n1 + half;
@@ -658,35 +682,40 @@ __global__ __launch_bounds__(64) void k_qkv_rope_store(Pass pass, const TreeDev*
 
 // ============================================================================ SwiGLU and logits epilogues
 // act[r][k] = silu(gate) * up with the fused matrix's row order (PACK_GATE / PACK_UP)   (F = d_ffn)
-__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, int S, int Npad, int Mpad, int F,
+// A wave owns one tile of the output (32 rows x one k-step of 16 features): lane = (row, half of the k-step), which is
+// the tile's own lane order, so the wave writes 1 KiB contiguous per plane; the lane's 8 gate and 8 up values are
+// 32 bytes each in the row's 128-byte line of the fused block, so the two lanes of a row read that line exactly once.
+// Grid (k-steps / 4, 32-row tiles); rows beyond M are written as zeros.
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ PT, int S, int Npad, int Mpad, int F, int M,
                                                 bf16_t* XF, int MT, int nplanes) {
-  int r = blockIdx.y;
-  int k8 = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
-  if (k8 >= F) return;
-  // the 8 gate rows of this chunk are contiguous in the fused matrix (PACK_GATE), the 8 up rows sit 16 further
-  const int ng = pack_row_map(PACK_GATE, k8, 0);
+  const int lane = threadIdx.x & 63, ks = blockIdx.x * 4 + (threadIdx.x >> 6), KSF = F / 16;
+  if (ks >= KSF) return;
+  const int r = blockIdx.y * 32 + (lane & 31), half = lane >> 5;
+  const int ng = 32 * ks + 8 * half;                 // this lane's 8 gate rows of the fused matrix; the up rows sit 16 further
   float gs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, us[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int s0 = 0; s0 < S; s0 += 4) {              // four splits' worth of loads in flight, added in split order
-    f32x4 g0[4], g1[4], u0[4], u1[4];
+  if (r < M) {
+    for (int s0 = 0; s0 < S; s0 += 4) {              // four splits' worth of loads in flight, added in split order
+      f32x4 g0[4], g1[4], u0[4], u1[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float* src = PT + ((size_t)min(s0 + q, S - 1) * Mpad + r) * Npad + ng;
-      g0[q] = *(const f32x4*)src; g1[q] = *(const f32x4*)(src + 4);
-      u0[q] = *(const f32x4*)(src + 16); u1[q] = *(const f32x4*)(src + 20);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (s0 + q < S) {
-        gs[0] += g0[q].x; gs[1] += g0[q].y; gs[2] += g0[q].z; gs[3] += g0[q].w;
-        gs[4] += g1[q].x; gs[5] += g1[q].y; gs[6] += g1[q].z; gs[7] += g1[q].w;
-        us[0] += u0[q].x; us[1] += u0[q].y; us[2] += u0[q].z; us[3] += u0[q].w;
-        us[4] += u1[q].x; us[5] += u1[q].y; us[6] += u1[q].z; us[7] += u1[q].w;
+      for (int q = 0; q < 4; ++q) {
+        const float* src = PT + ((size_t)min(s0 + q, S - 1) * Mpad + r) * Npad + ng;
+        g0[q] = *(const f32x4*)src; g1[q] = *(const f32x4*)(src + 4);
+        u0[q] = *(const f32x4*)(src + 16); u1[q] = *(const f32x4*)(src + 20);
       }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (s0 + q < S) {
+          gs[0] += g0[q].x; gs[1] += g0[q].y; gs[2] += g0[q].z; gs[3] += g0[q].w;
+          gs[4] += g1[q].x; gs[5] += g1[q].y; gs[6] += g1[q].z; gs[7] += g1[q].w;
+          us[0] += u0[q].x; us[1] += u0[q].y; us[2] += u0[q].z; us[3] += u0[q].w;
+          us[4] += u1[q].x; us[5] += u1[q].y; us[6] += u1[q].z; us[7] += u1[q].w;
+        }
+    }
   }
   float x[8];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) x[t] = gs[t] / (1.0f + __expf(-gs[t])) * us[t];
-  xf_store8(XF, r, k8, MT, F / 16, nplanes, x);
+  for (int t = 0; t < 8; ++t) x[t] = r < M ? gs[t] / (1.0f + __expf(-gs[t])) * us[t] : 0.f;
+  xf_store8(XF, r, 16 * ks + 8 * half, MT, KSF, nplanes, x);
 }
 
 // logits[dst_row(r)][v] = sum_s PT[s][v][r].  Where a pass's row maps to no output (padding rows, pending rows
