@@ -686,7 +686,9 @@ static hipError_t launch_gemm_mt(eagle_ctx* c, const PackedW& w, const bf16_t* X
 }
 
 // PT <- X (XF layout, MT row tiles) times W^T.  Returns the split count through *S.
-static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S) {
+// swiglu_out (gate/up matrices only): where the plan has a single K slice in the large-M kernel, the SwiGLU epilogue runs
+// inside the GEMM and its output goes to swiglu_out in GEMM-input layout; *S is then 0 (nothing left in PT).
+static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S, bf16_t* swiglu_out = nullptr, int M = 0) {
   const bool big = use_pf(c, MT);
   GemmPlan p = big ? plan_pf(w.NRB, w.KS, MT, c->n_cu) : plan_gemm(w.NRB, w.KS, c->NXP, MT);
   if ((size_t)p.S * w.Npad * MT * 32 > c->pt_floats) return fail(EAGLE_EINVAL, "internal: partial buffer too small");
@@ -695,11 +697,20 @@ static int gemm(eagle_ctx* c, const PackedW& w, const bf16_t* XF, int MT, int* S
   hipError_t e;
   if (big) {
     static bool attr_set = false;
-    if (!attr_set) { HIPCHK(hipFuncSetAttribute((const void*)k_gemm_pf<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_set = true; }
+    if (!attr_set) {
+      HIPCHK(hipFuncSetAttribute((const void*)k_gemm_pf<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+      HIPCHK(hipFuncSetAttribute((const void*)k_gemm_pf<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+      attr_set = true;
+    }
     const int MQ = (MT + 3) / 4, G = ((w.NRB + 7) / 8) * p.S;
     const int grid = (G + 7) / 8 * 8 * MQ;
-    e = launch_k(c, c->cur_class, (double)w.N * w.K * c->elt, "k_gemm_pf", k_gemm_pf<2>, dim3(grid), dim3(256), (size_t)64 * 1024,
-                 (const bf16_t*)w.w, XF, c->PT, w.NRB, w.KS, p.ks_per_split, p.S, w.Npad, MT);
+    if (swiglu_out && p.S == 1) {
+      *S = 0;
+      e = launch_k(c, c->cur_class, (double)w.N * w.K * c->elt, "k_gemm_pf<swiglu>", k_gemm_pf<2, true>, dim3(grid), dim3(256), (size_t)64 * 1024,
+                   (const bf16_t*)w.w, XF, c->PT, w.NRB, w.KS, p.ks_per_split, p.S, w.Npad, MT, swiglu_out, M);
+    } else
+    e = launch_k(c, c->cur_class, (double)w.N * w.K * c->elt, "k_gemm_pf", k_gemm_pf<2, false>, dim3(grid), dim3(256), (size_t)64 * 1024,
+                 (const bf16_t*)w.w, XF, c->PT, w.NRB, w.KS, p.ks_per_split, p.S, w.Npad, MT, (bf16_t*)nullptr, 0);
   } else e = c->f32 ? launch_gemm_mt<3, 3>(c, w, XF, c->PT, MT, p) : launch_gemm_mt<1, 2>(c, w, XF, c->PT, MT, p);
   if (e != hipSuccess) return fail(EAGLE_EHIP, "gemm launch failed: %s", hipGetErrorString(e));
   return EAGLE_OK;
@@ -818,8 +829,8 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     }
     return EAGLE_OK;
   }
-  if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.gu, c->xf_d, MT, &S)))) return rc;
-  {
+  if ((rc = (c->cur_class = KC_GATEUP, gemm(c, w.gu, c->xf_d, MT, &S, c->xf_ffn, M)))) return rc;
+  if (S > 0) {
     dim3 grid((F / 16 + 3) / 4, MT);
     k_swiglu<<<grid, 256, 0, c->stream>>>(c->PT, S, w.gu.Npad, MT * 32, F, M, c->xf_ffn, MT, c->NXP);
     LAUNCH_CHECK();

@@ -367,10 +367,15 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t* __restrict__ Wp, siz
 // Work-groups that share a weight tile (the activation-row tiles of one weight-row tile) get ids 8 apart, i.e. the same
 // XCD under round-robin dispatch, next to each other in dispatch order: the tile comes from HBM once and from that
 // XCD's L2 afterwards.
-template <int NXP>
+__device__ inline void xf_store8(bf16_t* XF, int m, int k8, int MT, int KS, int nplanes, const float* x);   // defined with the row producers below
+// SWIGLU (only with S = 1, gate/up matrices): instead of PT the kernel writes silu(gate) * up as the next GEMM's input
+// (XF layout, `act`, rows beyond M as zeros).  A row block of the fused matrix holds 16 gate rows and the 16 up rows of
+// the same features, and accumulator registers r and r + 8 of a lane are such a pair; the two lanes of an activation
+// row swap four values so that each holds 8 consecutive features = its 16 bytes of the output tile.
+template <int NXP, bool SWIGLU = false>
 __global__ __launch_bounds__(256, 2) void k_gemm_pf(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ XF,
                                                  float* __restrict__ PT, int NRB, int KS, int ks_per_split, int S, int Npad,
-                                                 int MT /*32-row tiles of the pass*/) {
+                                                 int MT /*32-row tiles of the pass*/, bf16_t* act = nullptr, int M = 0) {
   constexpr int CH = 4;                                         // k-steps per LDS stage
   constexpr int XT = NXP * 4 * CH;                              // activation tiles (1 KiB) per stage
   constexpr int XR = XT / CH;                                   // activation tiles per stage and k-step = loads per wave and stage
@@ -459,6 +464,35 @@ __global__ __launch_bounds__(256, 2) void k_gemm_pf(const bf16_t* __restrict__ W
     asm volatile("" ::: "memory");
   }
   // accumulator register r of lane l: weight row 8*(r/4) + 4*(l/32) + r%4, activation row l%32; PT[s][m][n], n fastest
+  if constexpr (SWIGLU) {
+    const int hh = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (!(j ? liveB : liveA)) continue;
+      const int rb = j ? rbB : rbA;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int mt = mq * 4 + t;
+        if (mt >= MT) continue;
+        const int m = mt * 32 + (lane & 31);
+        float v[8];                                             // features 4hh + {0..3} and 8 + 4hh + {0..3} of the block
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const float gs = acc[j][t][r], us = acc[j][t][r + 8];
+          v[r] = m < M ? gs / (1.0f + __expf(-gs)) * us : 0.f;
+        }
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float got = __shfl_xor(hh ? v[i] : v[4 + i], 32, 64);   // the partner's features 4..7 (for hh = 0) or 8..11 (for hh = 1)
+          x[i] = hh ? got : v[i];
+          x[4 + i] = hh ? v[4 + i] : got;
+        }
+        xf_store8(act, m, 16 * rb + 8 * hh, MT, NRB, NXP, x);
+      }
+    }
+    return;
+  }
   const int Mpad = MT * 32;
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
