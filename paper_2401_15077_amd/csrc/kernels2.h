@@ -1305,7 +1305,9 @@ __global__ __launch_bounds__(256) void k2_attn(Pass pass, const TreeDev* tree, S
     q_s[(1 * KSN + ks) * 64 + lane] = l8;
   }
   __syncthreads();
-  const int T = base + n_new;
+  // causal passes (prompt chunks, pending rows): the rows of this 32-row block see no new token beyond its own last row,
+  // so the blocks of keys after it are not visited at all (they would contribute exp(-inf) = 0: same bits, less work)
+  const int T = base + (r_first.causal ? min(n_new, 32 * rblk + R) : n_new);
   // the split boundaries depend on `base` only, so a row sees the same partition whatever else is in the pass
   const int span = base + max(64, (n_new + 63) / 64 * 64);   // passes with at most 64 new rows share one partition
   const int tps = ((span + n_splits - 1) / n_splits + 63) / 64 * 64;
