@@ -796,21 +796,41 @@ __device__ __forceinline__ void fk_stream_q4(const bf16_t* __restrict__ XF, int 
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int kk = 8 * g + 4 * st + ks;
-#pragma unroll
-        for (int j = 0; j < NR; ++j) {
+        auto expand = [&](int j) {
           const uint32_t wd = ks == 0 ? a4[st][j].x : ks == 1 ? a4[st][j].y : ks == 2 ? a4[st][j].z : a4[st][j].w;
           u32x4 av;
           av.x = (wd & 0x000F000Fu) | 0x43004300u;
           av.y = ((wd >> 4) & 0x000F000Fu) | 0x43004300u;
           av.z = ((wd >> 8) & 0x000F000Fu) | 0x43004300u;
           av.w = ((wd >> 12) & 0x000F000Fu) | 0x43004300u;
+          return av;
+        };
+        if constexpr (NR <= 2) {
+          // plane by plane, so that consecutive MFMAs write different accumulators (measured: QKV 20.4 -> 19.3 us, down
+          // 19.0 -> 17.8 us); with three row blocks the expanded operands held across the planes spill, so they keep the
+          // block-by-block order
+          u32x4 av[NR];
+#pragma unroll
+          for (int j = 0; j < NR; ++j) av[j] = expand(j);
+#pragma unroll
+          for (int q = 0; q < NXP; ++q) {
+#pragma unroll
+            for (int j = 0; j < NR; ++j)
+              part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[j]), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), part[j], 0, 0, 0);
+            sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), sx, 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < NR; ++j) {
+            const u32x4 av = expand(j);
+#pragma unroll
+            for (int q = 0; q < NXP; ++q)
+              part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), part[j], 0, 0, 0);
+          }
 #pragma unroll
           for (int q = 0; q < NXP; ++q)
-            part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), part[j], 0, 0, 0);
+            sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), sx, 0, 0, 0);
         }
-#pragma unroll
-        for (int q = 0; q < NXP; ++q)
-          sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, tb[4 * st + ks][q]), sx, 0, 0, 0);
         // use a slot, refill that slot: the same k-step of the next group
         (void)kk;
 #pragma unroll
