@@ -5,7 +5,7 @@ cpu_baseline leg of bench.py may import it.  It shares no code with the HIP path
 
 Plain numpy, one sequence at a time, no blocking / fusion / caching tricks: every function is the
 paper's step written out.  Arithmetic runs in `dtype` (float64 for small models; float32 for the
-LLaMA-sized shapes, the precision the build's contract names for the oracle).
+LLaMA-sized shapes, where float64 copies of the weights would not fit the host's memory).
 
 What follows which passage:
   * target forward, feature f = hidden state fed to the LM head, p = LM_Head(f)      -- Sec. 2 "Notations"
@@ -19,7 +19,7 @@ What follows which passage:
   * multi-round speculative sampling                                                    -- App. A.2, Alg. 1
   * chain rule min(1, p/q), resample from norm(max(0, p-q))                             -- Sec. 2 "Speculative sampling"
 
-Readings where the paper is silent or garbled (listed in full in the design notes of the repository):
+Readings where the paper is silent or garbled:
   * decoder layer = LLaMA-style pre-norm block (RMSNorm, rotate-half RoPE, GQA, SwiGLU / top-2 MoE)
   * the feature is taken AFTER the final RMSNorm (it is what the LM head consumes); the head's output
     goes to the LM head without a further norm

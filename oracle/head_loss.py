@@ -13,7 +13,7 @@ What the section fixes (notation as there; i runs over the positions of a traini
     L     = L_reg + w_cls * L_cls                 w_cls = 0.1
     augmentation: features of the target + U(-0.1, 0.1) noise
 
-Readings where the section is silent (listed with the other readings in the design notes):
+Readings where the section is silent:
   * Smooth L1 is the usual one with threshold 1: 0.5 x^2 for |x| < 1, |x| - 0.5 otherwise, averaged over every element
     of every row (rows * d terms).
   * Cross entropy with a distribution as the target: -sum_v p_v log p^_v per row, averaged over the rows.

@@ -4,8 +4,7 @@ head with int4-quantised weights; Table 4 reports the tokens/s).
 THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only tests/ and bench.py's cpu_baseline leg may import it.  It shares
 no code with the HIP path.
 
-The paper says nothing about the quantiser beyond "int4".  Reading taken by this build (listed with the other
-readings in the design notes): weight-only, group-wise along the input dimension, symmetric:
+The paper says nothing about the quantiser beyond "int4".  Reading taken here: weight-only, group-wise along the input dimension, symmetric:
 
     for every output row n and every group g of G = 128 consecutive input columns
         s[n, g]  = bf16( max_k |W[n, k]| / 7 )                      (round to nearest even; 0 if the group is all zero)
