@@ -58,3 +58,13 @@ def test_null_arguments_are_errors_not_crashes(lib):
     assert lib.eagle_step(None, None, None, None) == -1
     assert lib.eagle_init(None, None, 0, None, None) == -1
     assert lib.eagle_version().startswith(b"libeagle")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N > 1 exits with a message that says so (before touching torch)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "ONE GPU" in res.stderr
