@@ -61,6 +61,12 @@ def test_int4_llama13b_twin_lockstep():
     run_int4("llama2-13b", 2, "T26", 53, 40, 3, np.float32)
 
 
+def test_int4_llama70b_twin_lockstep():
+    """LLaMA2-70B widths (d 8192, 64 query heads on 8 KV heads, K = 28672: 224 groups; one row block per CU for O and
+    down), 2 target layers."""
+    run_int4("llama2-70b", 2, "T26", 54, 40, 3, np.float32)
+
+
 def test_int4_rejects_what_it_cannot_run():
     s = synth.SHAPES["tiny"]                                   # fp32 model
     par, rk = synth.TREES["T15"]
