@@ -263,7 +263,8 @@ class Eagle:
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         first = ctypes.c_int32()
         self._chk(self.lib.eagle_prefill(self.h, seq, _p32(p), len(p), ctypes.byref(first)))
-        chunk = 512 if (self.shape.dtype == "bf16" and self.shape.n_experts == 0) else 128
+        s = self.shape
+        chunk = 512 if (s.dtype == "bf16" and s.d_ffn % 64 == 0 and (s.n_heads * s.head_dim) % 64 == 0) else 128
         if self.weight_bits == 4:
             chunk = 32
         self.last_prefill_rows = (len(p) - 1) % chunk + 1          # rows of the prompt's last pass

@@ -115,7 +115,7 @@ struct eagle_ctx {
   // fast path (passes of <= 32 rows)
   float *h2, *PT2, *ssq1, *ssq2; int *cnt_gemm, *cnt_attn; size_t pt2_floats;
   bf16_t *xf2_d, *xf2_dB, *xf2_2d, *xf2_att, *xf2_ffn;
-  float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][128], used flags [E], fp32 normalised rows (general path)
+  float *moe_w, *xn; int* expert_used; int* experts_touched;   // (profiling) experts used, summed over the layers of a verify    // routing weights [E][largest pass], used flags [E], fp32 normalised rows (general path)
   int ssq1_groups = 0, ssq2_groups = 0;
   unsigned long long* trace = nullptr; int trace_sel = -1, gemm_no = 0, attn_trace_sel = -1, attn_no = 0, expand_trace = 0;   // profiling builds only
   int n_cu = 256;                      // compute units of the device (queried by eagle_init; 256 assumed when no device is visible)
@@ -381,7 +381,7 @@ static size_t layout(eagle_ctx* c) {
   c->h2 = a.take<float>((size_t)32 * d);
   c->xf2_d = a.take<bf16_t>((size_t)c->NXP * 32 * d);
   c->xf2_dB = a.take<bf16_t>(g.n_experts > 0 ? (size_t)c->NXP * 32 * d : 8);
-  c->moe_w = a.take<float>((size_t)std::max(1, g.n_experts) * 128);
+  c->moe_w = a.take<float>((size_t)std::max(1, g.n_experts) * c->Mmax);
   c->expert_used = a.take<int>(std::max(1, g.n_experts));
   c->experts_touched = a.take<int>(1);
   c->xn = a.take<float>(g.n_experts > 0 ? (size_t)Mm * d : 8);
@@ -435,7 +435,7 @@ static int prepare(const eagle_config* cfg, eagle_ctx* c) {
   for (int dlev = 1; dlev <= c->D; ++dlev) c->max_level_rows = std::max(c->max_level_rows, c->tree_h.n_level_rows[dlev]);
   if (cfg->max_batch * c->M > 128) return fail(EAGLE_EINVAL, "max_batch * n_nodes = %d rows exceeds the 128-row limit of one pass", cfg->max_batch * c->M);
   // (the large-M GEMM walks K in stages of 4 k-steps: every K of the model must be a multiple of 64)
-  c->pf_chunk = (!c->f32 && cfg->n_experts == 0 && cfg->d_ffn % 64 == 0 && (cfg->n_heads * cfg->head_dim) % 64 == 0) ? 512 : EAGLE_PREFILL_CHUNK;
+  c->pf_chunk = (!c->f32 && cfg->d_ffn % 64 == 0 && (cfg->n_heads * cfg->head_dim) % 64 == 0) ? 512 : EAGLE_PREFILL_CHUNK;
   if (c->q4) {
     // 4-bit weights exist in the fused kernels of the fast path only: every pass has at most 32 rows, the prompt included
     if (c->f32 || cfg->n_experts > 0) return fail(EAGLE_EINVAL, "weight_bits = 4 needs a dense bf16 model");
@@ -814,7 +814,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
     const int E = g.n_experts;
     k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->expert_used, 0u, (size_t)E);
     LAUNCH_CHECK();
-    k_router<<<M, 256, 0, c->stream>>>(c->xn, nullptr, nullptr, 0, 0.f, 0.f, nullptr, w.router, E, g.experts_per_tok, g.d_model, M, c->moe_w, 128, c->expert_used);
+    k_router<<<M, 256, 0, c->stream>>>(c->xn, nullptr, nullptr, 0, 0.f, 0.f, nullptr, w.router, E, g.experts_per_tok, g.d_model, M, c->moe_w, c->Mmax, c->expert_used);
     LAUNCH_CHECK();
     if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
@@ -825,7 +825,7 @@ static int layer_forward(eagle_ctx* c, const Pass& pass, int M, int MT, int li, 
       if ((rc = (c->cur_class = KC_DOWN, gemm(c, w.e_dn[e], c->xf_ffn, MT, &S)))) return rc;
       const bool last = e + 1 == E;     // only the last expert's pass produces the normalised output
       if ((rc = resnorm(c, M, MT, c->h, c->PT, S, w.e_dn[e].Npad, nullptr, last ? next_gain : nullptr, last ? c->xf_d : nullptr,
-                        last ? xout : nullptr, c->moe_w + (size_t)e * 128))) return rc;
+                        last ? xout : nullptr, c->moe_w + (size_t)e * c->Mmax))) return rc;
     }
     return EAGLE_OK;
   }
@@ -1141,7 +1141,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
     k_fill_u32<<<1, 64, 0, c->stream>>>((uint32_t*)c->expert_used, 0u, (size_t)E);
     LAUNCH_CHECK();
     k_router<<<M, 256, 0, c->stream>>>(nullptr, c->h2, c->ssq1, c->ssq1_groups, 1.0f / (float)d, cf.rms_eps, w.mlp_norm, w.router, E,
-                                       cf.experts_per_tok, d, M, c->moe_w, 128, c->expert_used);
+                                       cf.experts_per_tok, d, M, c->moe_w, c->Mmax, c->expert_used);
     LAUNCH_CHECK();
     if (c->prof_mode) { k_count_used<<<1, 64, 0, c->stream>>>(c->expert_used, E, c->experts_touched); LAUNCH_CHECK(); }
     for (int e = 0; e < E; ++e) {
@@ -1151,7 +1151,7 @@ static int layer2(eagle_ctx* c, const Pass& pass, int M, int li, int ctx_max, in
       if ((rc = (c->cur_class = KC_GATEUP, gemm2(c, w.e_gu[e], c->xf2_d, g, nullptr)))) return rc;
       g = gemm2_base(c, pass, M);
       g.epi = EPI_RESID; g.h_in = c->h2; g.h_out = c->h2; g.gain_next = next_gain; g.xf_out = c->xf2_dB; g.xf_KS = d / 16; g.ssq_out = c->ssq2;
-      g.row_w = c->moe_w + (size_t)e * 128; g.skip_flag = c->expert_used + e;
+      g.row_w = c->moe_w + (size_t)e * c->Mmax; g.skip_flag = c->expert_used + e;
       if ((rc = (c->cur_class = KC_DOWN, gemm2(c, w.e_dn[e], c->xf2_ffn, g, &c->ssq2_groups)))) return rc;
     }
     std::swap(c->xf2_d, c->xf2_dB);     // the experts all read the old xf2_d; the new one was built beside it
